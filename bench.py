@@ -1,0 +1,168 @@
+"""Throughput of the ragged encoder hot path on one MI355X.
+
+A step is one wf_encode_batch call over one synthetic batch (pack + hush append, conv stem, all
+transformer blocks, final LayerNorm) with the log-mel input already resident in HBM.  Prints ONE
+JSON line: encoded audio-seconds per second (payload audio, hush excluded), plus tokens/s, the
+fraction of the bf16 MFMA peak, the roofline of the dominant kernel (HIP-event durations measured
+here, on the launch stream) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops(shape, hush_frames, n_frames):
+    d, f, N, C = shape.d_model, shape.d_mlp, shape.n_layers, shape.n_mels
+    total = 0.0
+    for T in n_frames:
+        Tp = T + hush_frames
+        L = (Tp + 1) // 2
+        total += 2.0 * Tp * 3 * C * d                      # conv1: one d x 3C product per frame
+        total += 2.0 * L * 3 * d * d                       # conv2
+        total += N * (2.0 * L * d * (3 * d + d + 2 * f) + 4.0 * L * L * d)
+    return total
+
+
+def cpu_baseline(wl, weights, hush, mels, budget_flops=1.2e12):
+    """The oracle as it stands, timed on a bounded sample of the workload's streams."""
+    import numpy as np
+    from oracle import encoder_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    order = sorted(range(len(mels)), key=lambda i: len(mels[i]))
+    picks, fl = [], 0.0
+    for q in (0.125, 0.375, 0.625, 0.875, 0.25, 0.5, 0.75):      # spread over the length distribution
+        i = order[min(len(order) - 1, int(q * len(order)))]
+        if i in picks:
+            continue
+        fi = algorithmic_flops(wl.shape, wl.hush_frames, [len(mels[i])])
+        if picks and fl + fi > budget_flops:
+            continue
+        picks.append(i)
+        fl += fi
+    t0 = time.perf_counter()
+    O.encode_batch(weights, wl.shape.n_heads, [mels[i] for i in picks], hush if wl.hush_frames > 0 else None)
+    dt = time.perf_counter() - t0
+    audio_s = sum(len(mels[i]) for i in picks) / 100.0
+    return {"value": audio_s / dt, "unit": "audio-s/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(picks)} of {len(mels)} streams of {wl.name} ({[len(mels[i]) for i in picks]} frames), "
+                      f"NumPy fp64 oracle, {dt:.1f} s wall, {fl / dt / 1e9:.1f} GFLOP/s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (streams shard across GPUs without collectives; "
+              "no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload)
+    weights, hush, mels = synth.materialize(wl)
+    enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)
+    flat, offs, nf = wf.pack_mels(mels)
+    mel = torch.from_numpy(flat).cuda()
+    cu, total_frames, M = wf.plan_batch(enc.cfg, nf)
+    out = torch.empty((M, wl.shape.d_model), device="cuda", dtype=torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        enc.encode(mel, offs, nf, out=out, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # same steps again with every launch bracketed by HIP events on the launch stream
+    enc.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_prof = (time.perf_counter() - t0) / args.steps
+    stats = enc.kernel_stats()
+    enc.set_profiling(False)
+
+    payload_audio_s = float(sum(nf)) / synth.FRAMES_PER_SECOND
+    flops = algorithmic_flops(wl.shape, wl.hush_frames, nf)
+    kernels = {}
+    for s in stats:
+        if s["launches"] == 0:
+            continue
+        ms = s["total_ms"] / s["launches"]
+        kernels[s["name"]] = {"launches_per_step": s["launches"] // args.steps, "avg_ms": round(ms, 4),
+                              "share": round(s["total_ms"] / args.steps / (dt_prof * 1e3), 4),
+                              "tflops": round(s["flops"] / s["total_ms"] / 1e9, 1) if s["flops"] else None,
+                              "gbs": round(s["bytes"] / s["total_ms"] / 1e6, 1)}
+    mfma = [s for s in stats if s["flops"] > 0 and s["launches"] > 0]
+    dom = max(mfma, key=lambda s: s["total_ms"])
+    achieved = dom["flops"] / dom["total_ms"] / 1e9          # TFLOP/s
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom["name"])
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "avg_launch_ms": round(dom["total_ms"] / dom["launches"], 4),
+                "flops_per_launch": dom["flops"] / dom["launches"],
+                "ms_per_step_profiled": round(dt_prof * 1e3, 3)}
+
+    result = {
+        "metric": "encoded audio-sec/sec & tokens/sec per GPU; % of bf16 MFMA peak",
+        "value": round(payload_audio_s / dt, 1), "unit": "audio-s/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: large-v3-shaped encoder, 64 ragged streams" if wl.name == "cfg5" else wl.name,
+                   "streams": len(nf), "tokens": int(M), "frames_incl_hush": int(total_frames),
+                   "payload_audio_s": payload_audio_s, "d_model": wl.shape.d_model, "n_layers": wl.shape.n_layers},
+        "tokens_per_s": round(M / dt, 1),
+        "audio_s_per_s_incl_hush": round(total_frames / synth.FRAMES_PER_SECOND / dt, 1),
+        "algorithmic_tflops": round(flops / dt / 1e12, 1),
+        "pct_bf16_mfma_peak": round(100.0 * flops / dt / 1e12 / PEAK_BF16_TFLOPS, 2),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    enc.close()
+    del mel, out
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, weights, hush, mels)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

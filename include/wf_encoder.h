@@ -1,0 +1,188 @@
+/*
+ * wf_encoder.h -- C ABI of the ragged Whisper-style audio encoder for MI355X (gfx950).
+ *
+ * What the library computes (paper: WhisperFlow, arXiv 2412.11272):
+ *   Each processing round, every stream hands over a log-mel snapshot of its current audio buffer
+ *   (Section "Operations", processing rounds), of any length up to 30 s.  Instead of padding the
+ *   snapshot to a 30 s / 1500-token window, one fixed short segment -- the hush word, 0.5 s = 25
+ *   tokens, one per model -- is appended to it (Section "Hush word", hush word position: x (+) h)
+ *   and the encoder runs on that length only.  Different streams therefore have different lengths
+ *   (Section "Applicability" names this as the obstacle to batching); this library batches them
+ *   anyway by packing all streams' tokens back to back and restricting attention to each stream.
+ *   The encoder itself is the dense stage of a round (Section "CPU/GPU pipelining", categorization
+ *   of workloads, item 1): log-mel -> Conv1d(k3)+GELU -> Conv1d(k3, stride 2)+GELU -> + sinusoidal
+ *   positions -> n_layers pre-LN transformer blocks (bidirectional multi-head attention, GELU MLP)
+ *   -> LayerNorm.  T mel frames (100 per second) become floor((T+1)/2) tokens.
+ *   The hush word lives here at the log-mel level (a [hush_frames, n_mels] block); the paper appends
+ *   at the raw-audio level (Section "Hush word", target level).
+ *
+ * Conventions
+ *   - Every function returns WF_OK (0) or a negative WF_E_* code; nothing throws or exits.
+ *     wf_last_error() gives a thread-local text for the last failure on the calling thread.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory on the GPU
+ *     that was current when the encoder was created.  The library never frees caller memory.
+ *   - All matrices are row-major.  Linear weights are [out_features, in_features]; convolution
+ *     kernels are [out_channels, in_channels, 3] (tap 0 multiplies frame t-1, tap 2 frame t+1 for
+ *     the first convolution; frames 2j-1, 2j, 2j+1 for output token j of the second).
+ *   - Log-mel input is time-major [frames, n_mels].
+ */
+#ifndef WF_ENCODER_H
+#define WF_ENCODER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WF_OK            0
+#define WF_E_INVALID_ARG (-1)   /* NULL pointer, bad shape, bad length, bad dtype                */
+#define WF_E_CAPACITY    (-2)   /* batch exceeds the capacity given at create, or out_capacity   */
+#define WF_E_OOM         (-3)   /* device or host allocation failed                              */
+#define WF_E_HIP         (-4)   /* a HIP runtime call or kernel launch failed                    */
+
+#define WF_DTYPE_F32  0
+#define WF_DTYPE_BF16 1
+
+#define WF_PRECISION_BF16 0     /* bf16 MFMA with fp32 accumulation, fp32 residual stream        */
+#define WF_PRECISION_F32  1     /* debug path: fp32 storage and arithmetic everywhere            */
+
+typedef struct wf_encoder wf_encoder;   /* opaque; owned by the library */
+
+typedef struct {
+  int32_t n_mels;                /* log-mel bins per frame; multiple of 8                          */
+  int32_t d_model;               /* multiple of 128; d_model / n_heads must be 64                  */
+  int32_t n_layers;              /* >= 0                                                           */
+  int32_t n_heads;
+  int32_t d_mlp;                 /* multiple of 128                                                */
+  int32_t hush_frames;           /* H >= 0; 0 disables the append (padded-window baseline)         */
+  int32_t max_streams;           /* capacity: streams per call                                     */
+  int32_t max_total_frames;      /* capacity: sum over streams of (n_frames + H) per call          */
+  int32_t max_frames_per_stream; /* capacity: n_frames + H of any one stream                       */
+  int32_t precision;             /* WF_PRECISION_*                                                 */
+  float   ln_eps;                /* LayerNorm epsilon; <= 0 selects 1e-5                           */
+} wf_config;
+
+/* Weights of one pre-LN block.  All HOST pointers, fp32.  bk may be NULL (no key bias). */
+typedef struct {
+  const float *ln1_g, *ln1_b;    /* [d]                */
+  const float *wq, *bq;          /* [d, d], [d]        */
+  const float *wk, *bk;          /* [d, d], [d] | NULL */
+  const float *wv, *bv;          /* [d, d], [d]        */
+  const float *wo, *bo;          /* [d, d], [d]        */
+  const float *ln2_g, *ln2_b;    /* [d]                */
+  const float *w1, *b1;          /* [d_mlp, d], [d_mlp]*/
+  const float *w2, *b2;          /* [d, d_mlp], [d]    */
+} wf_layer_weights;
+
+/* All HOST pointers, fp32.  The library copies and converts them in wf_encoder_create; the caller
+ * may free them as soon as it returns. */
+typedef struct {
+  const float *conv1_w, *conv1_b;        /* [d, n_mels, 3], [d]                                    */
+  const float *conv2_w, *conv2_b;        /* [d, d, 3], [d]                                         */
+  const float *hush_mel;                 /* [hush_frames, n_mels]; may be NULL iff hush_frames == 0 */
+  const wf_layer_weights *layers;        /* [n_layers]                                             */
+  const float *lnf_g, *lnf_b;            /* [d]                                                    */
+} wf_weights;
+
+/*
+ * Create an encoder on the current HIP device: validates the configuration, uploads the weights
+ * (rounded to bf16, round-to-nearest-even, in WF_PRECISION_BF16), the hush segment and the
+ * sinusoidal position table P[j, c] = sin(j w_c), P[j, d/2 + c] = cos(j w_c),
+ * w_c = 10000^(-c/(d/2 - 1)), and allocates a workspace sized from the three capacities.
+ * Errors: WF_E_INVALID_ARG (NULL, bad shape), WF_E_OOM, WF_E_HIP.  On error *out is NULL.
+ */
+int wf_encoder_create(const wf_config *cfg, const wf_weights *weights, wf_encoder **out);
+
+/*
+ * Encode one ragged batch (the hot path).
+ *
+ *   mel_dev       device; log-mel frames, [*, n_mels] time-major, dtype mel_dtype (WF_DTYPE_*).
+ *   frame_offset  host [B]; index (in frames) of stream i's first frame inside mel_dev.  Padded
+ *                 layouts (i * T_max) and packed layouts (prefix sums) are both expressible.
+ *   n_frames      host [B]; T_i >= 1 payload frames of stream i.
+ *   B             1 <= B <= max_streams.
+ *   out_dev       device; receives the encoder states, [M, d_model] packed stream-major, dtype
+ *                 out_dtype; M = sum_i floor((T_i + H + 1) / 2).  Stream i occupies rows
+ *                 [cu_seqlens[i], cu_seqlens[i+1]).
+ *   out_capacity_tokens  rows available in out_dev.
+ *   cu_seqlens_host      host [B+1], may be NULL; written before the call returns (computed on the
+ *                 host from n_frames, no device synchronisation involved).
+ *   hip_stream    a hipStream_t (NULL = the default stream).  All work is enqueued on it and the
+ *                 call returns without waiting; the caller synchronises before reading out_dev.
+ *
+ * Host-side validation happens before anything is enqueued: WF_E_INVALID_ARG for NULL pointers,
+ * B < 1, T_i < 1, negative offsets or unknown dtypes; WF_E_CAPACITY if B > max_streams,
+ * T_i + H > max_frames_per_stream, sum(T_i + H) > max_total_frames or M > out_capacity_tokens.
+ * An encoder owns one workspace: calls on the same encoder must not overlap in time (enqueue
+ * them on one stream, or synchronise between streams).
+ */
+int wf_encode_batch(wf_encoder *enc,
+                    const void *mel_dev, int32_t mel_dtype,
+                    const int32_t *frame_offset, const int32_t *n_frames, int32_t B,
+                    void *out_dev, int32_t out_dtype, int64_t out_capacity_tokens,
+                    int32_t *cu_seqlens_host,
+                    void *hip_stream);
+
+/* Free everything the encoder owns (waits for the device to finish first).  NULL is accepted. */
+void wf_encoder_destroy(wf_encoder *enc);
+
+/* Thread-local description of the last error on this thread ("" if none). */
+const char *wf_last_error(void);
+
+/*
+ * Host-only helper (no GPU needed): validates lengths exactly as wf_encode_batch does and writes
+ * cu_seqlens[B+1] (token prefix sums), *total_frames = sum(T_i + H) and *total_tokens = M.
+ * Output pointers may be NULL.  Same error codes as wf_encode_batch.
+ */
+int wf_plan_batch(const wf_config *cfg, const int32_t *n_frames, int32_t B,
+                  int32_t *cu_seqlens, int64_t *total_frames, int64_t *total_tokens);
+
+/* Host-only: validates a configuration as wf_encoder_create would (WF_OK or WF_E_INVALID_ARG). */
+int wf_config_check(const wf_config *cfg);
+
+/*
+ * Per-kernel timing, measured with HIP events on the stream the kernels are launched on.
+ * wf_encoder_set_profiling(enc, 1) makes later wf_encode_batch calls bracket every kernel launch
+ * with a pair of events; wf_encoder_kernel_stats waits for the device, then adds up the elapsed
+ * times by kernel class and resets the counters.  Classes are indexed 0 .. wf_kernel_class_count()-1.
+ */
+typedef struct {
+  const char *name;     /* static string, e.g. "gemm_fc1" */
+  int64_t launches;     /* launches since the last wf_encoder_kernel_stats call */
+  double  total_ms;     /* sum of their durations */
+  double  flops;        /* algorithmic flops of those launches (0 for bandwidth kernels) */
+  double  bytes;        /* algorithmic HBM bytes of those launches (operands read + results written once) */
+} wf_kernel_stat;
+
+int wf_kernel_class_count(void);
+int wf_encoder_set_profiling(wf_encoder *enc, int32_t enabled);
+int wf_encoder_kernel_stats(wf_encoder *enc, wf_kernel_stat *stats, int32_t n_stats);
+
+/*
+ * Operator-level entry points: single steps of the encoder on caller-provided DEVICE buffers, for
+ * per-operator checks and micro-benchmarks.  precision selects the kernel family and the element
+ * type of activations and weights (WF_PRECISION_BF16: bf16, WF_PRECISION_F32: fp32).
+ *
+ * wf_op_linear      out = epilogue(a . w^T + bias); a [M, K], w [N, K], bias fp32 [N]; N % 128 == 0,
+ *                   K % 64 == 0.  epilogue 0: out [M, N] in the activation type; 1: GELU, same type;
+ *                   2: out is fp32 [M, N] and is updated in place, out += a . w^T + bias.
+ *                   (the projections of a transformer block: QKV, fc1, and out-projection / fc2)
+ * wf_op_layernorm   out[r, :] = (x[r, :] - mean) / sqrt(biased var + eps) * g + b, x fp32 [M, d],
+ *                   out dtype WF_DTYPE_*; d % 4 == 0, d <= 2048.
+ * wf_op_attention   bidirectional softmax attention restricted to each stream, head size 64:
+ *                   qkv [M, 3 * 64 * n_heads] (q | k | v), out [M, 64 * n_heads], cu_seqlens_host
+ *                   [B+1] with cu_seqlens_host[0] == 0 and no empty stream.  Allocates a small
+ *                   index buffer and waits for hip_stream before returning (the others are async).
+ */
+int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const float *bias_dev, void *out_dev,
+                 int32_t M, int32_t N, int32_t K, int32_t epilogue, void *hip_stream);
+int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, void *out_dev, int32_t out_dtype,
+                    int32_t M, int32_t d, float eps, void *hip_stream);
+int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
+                    int32_t n_heads, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WF_ENCODER_H */

@@ -67,7 +67,7 @@ def conv1d_k3(x: np.ndarray, w: np.ndarray, b: np.ndarray, stride: int) -> np.nd
     out = np.broadcast_to(b, (t_out, w.shape[0])).astype(x.dtype).copy()
     for k in range(3):
         rows = xp[k:k + stride * (t_out - 1) + 1:stride]      # rows stride*t + k of the padded input
-        out += rows @ w[:, :, k].T
+        out += rows @ np.ascontiguousarray(w[:, :, k]).T       # tap k as a [C_in, C_out] matrix product
     return out
 
 

@@ -1,0 +1,235 @@
+"""ctypes binding of libwf_encoder.so: the same entry points as include/wf_encoder.h, argument
+marshalling only.  PyTorch appears here solely as the owner of device buffers and streams.
+
+There is no fallback: if the shared library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwf_encoder.so")
+
+WF_OK, WF_E_INVALID_ARG, WF_E_CAPACITY, WF_E_OOM, WF_E_HIP = 0, -1, -2, -3, -4
+WF_DTYPE_F32, WF_DTYPE_BF16 = 0, 1
+WF_PRECISION_BF16, WF_PRECISION_F32 = 0, 1
+
+_fp = C.POINTER(C.c_float)
+_ip = C.POINTER(C.c_int32)
+
+
+class WfConfig(C.Structure):
+    _fields_ = [("n_mels", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32), ("n_heads", C.c_int32),
+                ("d_mlp", C.c_int32), ("hush_frames", C.c_int32), ("max_streams", C.c_int32),
+                ("max_total_frames", C.c_int32), ("max_frames_per_stream", C.c_int32), ("precision", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+_LAYER_FIELDS = ["ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"]
+
+
+class WfLayerWeights(C.Structure):
+    _fields_ = [(n, _fp) for n in _LAYER_FIELDS]
+
+
+class WfWeights(C.Structure):
+    _fields_ = [("conv1_w", _fp), ("conv1_b", _fp), ("conv2_w", _fp), ("conv2_b", _fp), ("hush_mel", _fp),
+                ("layers", C.POINTER(WfLayerWeights)), ("lnf_g", _fp), ("lnf_b", _fp)]
+
+
+class WfKernelStat(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+class WfError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"wf error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_last_error", "wf_plan_batch",
+           "wf_config_check", "wf_kernel_class_count", "wf_encoder_set_profiling", "wf_encoder_kernel_stats",
+           "wf_op_linear", "wf_op_layernorm", "wf_op_attention"]
+
+
+def lib() -> C.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2412_11272_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    L.wf_last_error.restype = C.c_char_p
+    L.wf_encoder_create.argtypes = [C.POINTER(WfConfig), C.POINTER(WfWeights), C.POINTER(C.c_void_p)]
+    L.wf_encode_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _ip, _ip, C.c_int32, C.c_void_p, C.c_int32,
+                                  C.c_int64, _ip, C.c_void_p]
+    L.wf_encoder_destroy.argtypes = [C.c_void_p]
+    L.wf_encoder_destroy.restype = None
+    L.wf_plan_batch.argtypes = [C.POINTER(WfConfig), _ip, C.c_int32, _ip, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.wf_config_check.argtypes = [C.POINTER(WfConfig)]
+    L.wf_encoder_set_profiling.argtypes = [C.c_void_p, C.c_int32]
+    L.wf_encoder_kernel_stats.argtypes = [C.c_void_p, C.POINTER(WfKernelStat), C.c_int32]
+    L.wf_op_linear.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                               C.c_int32, C.c_int32, C.c_void_p]
+    L.wf_op_layernorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_float, C.c_void_p]
+    L.wf_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, _ip, C.c_int32, C.c_int32, C.c_void_p]
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != WF_OK:
+        raise WfError(rc, lib().wf_last_error().decode())
+
+
+def last_error() -> str:
+    return lib().wf_last_error().decode()
+
+
+def make_config(shape, hush_frames: int, max_streams: int, max_total_frames: int, max_frames_per_stream: int,
+                precision: int = WF_PRECISION_BF16, ln_eps: float = 1e-5) -> WfConfig:
+    return WfConfig(shape.n_mels, shape.d_model, shape.n_layers, shape.n_heads, shape.d_mlp, hush_frames, max_streams,
+                    max_total_frames, max_frames_per_stream, precision, ln_eps)
+
+
+def config_check(cfg: WfConfig) -> int:
+    return lib().wf_config_check(C.byref(cfg))
+
+
+def plan_batch(cfg: WfConfig, n_frames: Sequence[int]) -> Tuple[np.ndarray, int, int]:
+    """Host-only planner: returns (cu_seqlens, total_frames, total_tokens) or raises WfError."""
+    B = len(n_frames)
+    nf = np.ascontiguousarray(n_frames, dtype=np.int32)
+    cu = np.zeros(B + 1, dtype=np.int32)
+    tf, tt = C.c_int64(0), C.c_int64(0)
+    _check(lib().wf_plan_batch(C.byref(cfg), nf.ctypes.data_as(_ip), B, cu.ctypes.data_as(_ip), C.byref(tf), C.byref(tt)))
+    return cu, tf.value, tt.value
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class Encoder:
+    """Owns one wf_encoder.  weights: the dict layout of synth.make_weights (host fp32 arrays)."""
+
+    def __init__(self, cfg: WfConfig, weights: dict, hush: Optional[np.ndarray]):
+        self.cfg = cfg
+        self._h = C.c_void_p(None)
+        keep: List[np.ndarray] = []          # host arrays must outlive the create call only
+
+        def p(a):
+            if a is None:
+                return None
+            a = _f32(a)
+            keep.append(a)
+            return a.ctypes.data_as(_fp)
+
+        n_layers = len(weights["layers"])
+        layers = (WfLayerWeights * max(n_layers, 1))()
+        for i, lw in enumerate(weights["layers"]):
+            for name in _LAYER_FIELDS:
+                setattr(layers[i], name, p(lw.get(name)))
+        w = WfWeights(p(weights["conv1_w"]), p(weights["conv1_b"]), p(weights["conv2_w"]), p(weights["conv2_b"]),
+                      p(hush) if (hush is not None and len(hush) > 0) else None,
+                      layers, p(weights["lnf_g"]), p(weights["lnf_b"]))
+        _check(lib().wf_encoder_create(C.byref(cfg), C.byref(w), C.byref(self._h)))
+
+    def encode(self, mel, frame_offset: Sequence[int], n_frames: Sequence[int], out=None, out_dtype=None, stream=None):
+        """mel: CUDA tensor [*, n_mels] (float32 or bfloat16).  Returns (out [M, d] CUDA tensor, cu_seqlens ndarray).
+        Asynchronous on `stream` (default: torch's current stream)."""
+        import torch
+        B = len(n_frames)
+        cu, _, M = plan_batch(self.cfg, n_frames) if 1 <= B <= self.cfg.max_streams else (np.zeros(B + 1, np.int32), 0, 0)
+        if out is None:
+            out = torch.empty((M, self.cfg.d_model), device=mel.device, dtype=out_dtype or torch.float32)
+        s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        off = np.ascontiguousarray(frame_offset, dtype=np.int32)
+        nf = np.ascontiguousarray(n_frames, dtype=np.int32)
+        cu_out = np.zeros(B + 1, dtype=np.int32)
+        _check(lib().wf_encode_batch(self._h, C.c_void_p(mel.data_ptr()), _torch_dtype_code(mel.dtype),
+                                     off.ctypes.data_as(_ip), nf.ctypes.data_as(_ip), B,
+                                     C.c_void_p(out.data_ptr()), _torch_dtype_code(out.dtype), out.shape[0],
+                                     cu_out.ctypes.data_as(_ip), C.c_void_p(s)))
+        return out, cu_out
+
+    def set_profiling(self, on: bool):
+        _check(lib().wf_encoder_set_profiling(self._h, 1 if on else 0))
+
+    def kernel_stats(self) -> List[dict]:
+        n = lib().wf_kernel_class_count()
+        st = (WfKernelStat * n)()
+        _check(lib().wf_encoder_kernel_stats(self._h, st, n))
+        return [{"name": s.name.decode(), "launches": s.launches, "total_ms": s.total_ms, "flops": s.flops, "bytes": s.bytes}
+                for s in st]
+
+    def close(self):
+        if self._h:
+            lib().wf_encoder_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _torch_dtype_code(dt) -> int:
+    import torch
+    if dt == torch.float32:
+        return WF_DTYPE_F32
+    if dt == torch.bfloat16:
+        return WF_DTYPE_BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def pack_mels(mels: Sequence[np.ndarray]):
+    """Concatenate per-stream host buffers into one [sum T_i, n_mels] array + (frame_offset, n_frames)."""
+    n_frames = [int(m.shape[0]) for m in mels]
+    offs = np.concatenate([[0], np.cumsum(n_frames)[:-1]]).astype(np.int32)
+    return np.concatenate(mels, axis=0).astype(np.float32), offs, np.asarray(n_frames, np.int32)
+
+
+def encoder_for_workload(wl, weights, hush, precision: int = WF_PRECISION_BF16, slack_streams: int = 0) -> Encoder:
+    """Capacity sized exactly for one workload."""
+    per = [(m if wl.pad_to_frames is None else max(m, wl.pad_to_frames)) + wl.hush_frames for m in wl.n_frames]
+    cfg = make_config(wl.shape, wl.hush_frames, len(per) + slack_streams, sum(per), max(per), precision)
+    return Encoder(cfg, weights, hush)
+
+
+# ---- operator-level entry points ---------------------------------------------------------------
+def op_linear(precision: int, a, w, bias, out, epilogue: int, stream=None):
+    import torch
+    M, K = a.shape
+    N = w.shape[0]
+    s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().wf_op_linear(precision, C.c_void_p(a.data_ptr()), C.c_void_p(w.data_ptr()), C.c_void_p(bias.data_ptr()),
+                              C.c_void_p(out.data_ptr()), M, N, K, epilogue, C.c_void_p(s)))
+    return out
+
+
+def op_layernorm(x, g, b, out, eps: float = 1e-5, stream=None):
+    import torch
+    M, d = x.shape
+    s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().wf_op_layernorm(C.c_void_p(x.data_ptr()), C.c_void_p(g.data_ptr()), C.c_void_p(b.data_ptr()),
+                                 C.c_void_p(out.data_ptr()), _torch_dtype_code(out.dtype), M, d, eps, C.c_void_p(s)))
+    return out
+
+
+def op_attention(precision: int, qkv, out, cu_seqlens: Sequence[int], n_heads: int, stream=None):
+    import torch
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().wf_op_attention(precision, C.c_void_p(qkv.data_ptr()), C.c_void_p(out.data_ptr()), cu.ctypes.data_as(_ip),
+                                 len(cu) - 1, n_heads, C.c_void_p(s)))
+    return out

@@ -1,0 +1,616 @@
+// Host runtime of the ragged encoder: configuration checks, weight upload, the ragged-batch
+// planner (prefix sums, attention work list) and the launch sequence behind the C ABI declared in
+// include/wf_encoder.h.  Everything device-side is in the kernel files; this file only sequences
+// them on the caller's stream.
+#include "../../include/wf_encoder.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace wf;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess) return fail(e_ == hipErrorOutOfMemory ? WF_E_OOM : WF_E_HIP,        \
+                                      "%s: %s", #expr, hipGetErrorString(e_));                \
+  } while (0)
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// float -> bf16 bits, round to nearest even (NaN kept quiet).
+inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+enum KClass : int {
+  KC_PREP = 0, KC_CONV1, KC_CONV2, KC_LN, KC_QKV, KC_ATTN, KC_OUT, KC_FC1, KC_FC2, KC_LNF, KC_COUNT
+};
+const char *const kClassNames[KC_COUNT] = {"prep_pack_hush", "conv1_gemm_gelu", "conv2_gemm_gelu_pos", "layernorm",
+                                           "gemm_qkv", "attention", "gemm_out_resid", "gemm_fc1_gelu",
+                                           "gemm_fc2_resid", "layernorm_final"};
+
+struct LayerDev {
+  float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+  void *wqkv, *wo, *w1, *w2;          // act dtype
+  float *bqkv, *bo, *b1, *b2;
+};
+
+struct ProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
+
+constexpr int kStagingSlots = 4;
+
+}  // namespace
+
+struct wf_encoder {
+  wf_config cfg{};
+  int device = 0;
+  bool bf16 = true;
+  int es = 2;                           // bytes per activation/weight element
+  int k1p = 0;                          // padded reduction length of the first convolution
+  int64_t max_tokens = 0, max_work = 0, max_pos = 0;
+  std::vector<void *> allocs;           // every device allocation, for destroy
+  // weights
+  void *conv1_w = nullptr, *conv2_w = nullptr, *hush = nullptr;
+  float *conv1_b = nullptr, *conv2_b = nullptr, *lnf_g = nullptr, *lnf_b = nullptr, *pos = nullptr;
+  std::vector<LayerDev> layers;
+  // workspace
+  void *packed = nullptr, *G = nullptr, *u = nullptr, *qkv = nullptr, *h = nullptr;
+  float *x = nullptr;
+  int32_t *frame_src = nullptr, *frame_flags = nullptr, *tok_src = nullptr, *tok_flags = nullptr, *tok_pos = nullptr;
+  int32_t *idx_dev = nullptr;
+  int64_t idx_ints = 0;
+  // pinned staging ring for the small per-call index arrays
+  int32_t *stage_host[kStagingSlots] = {};
+  hipEvent_t stage_evt[kStagingSlots] = {};
+  bool stage_used[kStagingSlots] = {};
+  int stage_next = 0;
+  // profiling
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> evt_pool;
+};
+
+namespace {
+
+int dev_alloc(wf_encoder *e, void **p, size_t bytes) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 256;
+  hipError_t err = hipMalloc(p, bytes);
+  if (err != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(WF_E_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(err));
+  }
+  e->allocs.push_back(*p);
+  return WF_OK;
+}
+
+// Upload n floats as fp32.
+int upload_f32(wf_encoder *e, float **dst, const float *src, size_t n) {
+  int rc = dev_alloc(e, (void **)dst, n * 4);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpy(*dst, src, n * 4, hipMemcpyHostToDevice));
+  return WF_OK;
+}
+
+// Upload a host fp32 matrix in the encoder's weight dtype (bf16 RNE or fp32).
+int upload_w(wf_encoder *e, void **dst, const std::vector<float> &src) {
+  int rc = dev_alloc(e, dst, src.size() * e->es);
+  if (rc) return rc;
+  if (e->bf16) {
+    std::vector<uint16_t> tmp(src.size());
+    for (size_t i = 0; i < src.size(); ++i) tmp[i] = f32_to_bf16_rne(src[i]);
+    HIP_TRY(hipMemcpy(*dst, tmp.data(), tmp.size() * 2, hipMemcpyHostToDevice));
+  } else {
+    HIP_TRY(hipMemcpy(*dst, src.data(), src.size() * 4, hipMemcpyHostToDevice));
+  }
+  return WF_OK;
+}
+
+// Convolution kernel [c_out, c_in, 3] -> GEMM weight [c_out, kp], column k*c_in + m = W[c, m, k],
+// zero in the padding columns.
+std::vector<float> conv_as_gemm_weight(const float *w, int c_out, int c_in, int kp) {
+  std::vector<float> r((size_t)c_out * kp, 0.0f);
+  for (int c = 0; c < c_out; ++c)
+    for (int m = 0; m < c_in; ++m)
+      for (int k = 0; k < 3; ++k) r[(size_t)c * kp + k * c_in + m] = w[((size_t)c * c_in + m) * 3 + k];
+  return r;
+}
+
+struct Plan {
+  int64_t total_frames = 0, total_tokens = 0;
+};
+
+// Shared by wf_plan_batch and wf_encode_batch: validates and fills cu_frames / cu_seqlens (either may be NULL).
+int plan_batch(const wf_config &c, const int32_t *n_frames, int32_t B, int32_t *cu_frames, int32_t *cu_seqlens, Plan *plan) {
+  if (!n_frames) return fail(WF_E_INVALID_ARG, "n_frames is NULL");
+  if (B < 1) return fail(WF_E_INVALID_ARG, "B = %d, need B >= 1", B);
+  if (B > c.max_streams) return fail(WF_E_CAPACITY, "B = %d exceeds max_streams = %d", B, c.max_streams);
+  int64_t tf = 0, tt = 0;
+  if (cu_frames) cu_frames[0] = 0;
+  if (cu_seqlens) cu_seqlens[0] = 0;
+  for (int i = 0; i < B; ++i) {
+    const int64_t T = n_frames[i];
+    if (T < 1) return fail(WF_E_INVALID_ARG, "n_frames[%d] = %lld, need >= 1", i, (long long)T);
+    const int64_t Tp = T + c.hush_frames;
+    if (Tp > c.max_frames_per_stream)
+      return fail(WF_E_CAPACITY, "stream %d: %lld frames incl. hush exceed max_frames_per_stream = %d", i, (long long)Tp,
+                  c.max_frames_per_stream);
+    tf += Tp;
+    tt += (Tp + 1) / 2;
+    if (tf > c.max_total_frames)
+      return fail(WF_E_CAPACITY, "total frames incl. hush exceed max_total_frames = %d (at stream %d)", c.max_total_frames, i);
+    if (cu_frames) cu_frames[i + 1] = (int32_t)tf;
+    if (cu_seqlens) cu_seqlens[i + 1] = (int32_t)tt;
+  }
+  plan->total_frames = tf;
+  plan->total_tokens = tt;
+  return WF_OK;
+}
+
+int check_config(const wf_config *c) {
+  if (!c) return fail(WF_E_INVALID_ARG, "cfg is NULL");
+  if (c->n_mels < 8 || c->n_mels % 8) return fail(WF_E_INVALID_ARG, "n_mels = %d must be a positive multiple of 8", c->n_mels);
+  if (c->d_model < 128 || c->d_model % 128) return fail(WF_E_INVALID_ARG, "d_model = %d must be a positive multiple of 128", c->d_model);
+  if (c->n_heads < 1 || c->d_model != c->n_heads * 64)
+    return fail(WF_E_INVALID_ARG, "d_model / n_heads must be 64 (d_model = %d, n_heads = %d)", c->d_model, c->n_heads);
+  if (c->d_mlp < 128 || c->d_mlp % 128) return fail(WF_E_INVALID_ARG, "d_mlp = %d must be a positive multiple of 128", c->d_mlp);
+  if (c->n_layers < 0) return fail(WF_E_INVALID_ARG, "n_layers = %d", c->n_layers);
+  if (c->hush_frames < 0) return fail(WF_E_INVALID_ARG, "hush_frames = %d", c->hush_frames);
+  if (c->max_streams < 1) return fail(WF_E_INVALID_ARG, "max_streams = %d", c->max_streams);
+  if (c->max_frames_per_stream < 1 + c->hush_frames)
+    return fail(WF_E_INVALID_ARG, "max_frames_per_stream = %d cannot hold one frame plus the hush segment", c->max_frames_per_stream);
+  if (c->max_total_frames < c->max_frames_per_stream)
+    return fail(WF_E_INVALID_ARG, "max_total_frames = %d < max_frames_per_stream = %d", c->max_total_frames, c->max_frames_per_stream);
+  if (c->precision != WF_PRECISION_BF16 && c->precision != WF_PRECISION_F32)
+    return fail(WF_E_INVALID_ARG, "precision = %d", c->precision);
+  if (c->d_model > 2048) return fail(WF_E_INVALID_ARG, "d_model = %d exceeds the supported 2048", c->d_model);
+  return WF_OK;
+}
+
+hipEvent_t get_event(wf_encoder *e) {
+  if (!e->evt_pool.empty()) {
+    hipEvent_t ev = e->evt_pool.back();
+    e->evt_pool.pop_back();
+    return ev;
+  }
+  hipEvent_t ev = nullptr;
+  if (hipEventCreate(&ev) != hipSuccess) return nullptr;
+  return ev;
+}
+
+// Brackets one launch with events when profiling is on.
+struct Scope {
+  wf_encoder *e;
+  hipStream_t s;
+  ProfRec rec{};
+  bool on;
+  Scope(wf_encoder *enc, hipStream_t st, int cls, double flops, double bytes) : e(enc), s(st), on(enc->profiling) {
+    if (!on) return;
+    rec.cls = cls; rec.flops = flops; rec.bytes = bytes;
+    rec.t0 = get_event(e); rec.t1 = get_event(e);
+    if (!rec.t0 || !rec.t1) { on = false; return; }
+    (void)hipEventRecord(rec.t0, s);
+  }
+  ~Scope() {
+    if (!on) return;
+    (void)hipEventRecord(rec.t1, s);
+    e->prof.push_back(rec);
+  }
+};
+
+// a_rows x a_cols: the part of the activation operand the launch reads (once, algorithmically).
+int run_gemm(wf_encoder *e, hipStream_t s, int cls, const GemmArgs &a, AMode am, Epilogue ep, int k_real, int out_bytes,
+             double a_rows, double a_cols) {
+  const double flops = 2.0 * a.M * a.N * k_real;
+  double bytes = a_rows * a_cols * e->es + (double)a.N * k_real * e->es + (double)a.M * a.N * out_bytes;
+  if (ep == EPI_BIAS_RESID) bytes += (double)a.M * a.N * 4;
+  Scope sc(e, s, cls, flops, bytes);
+  hipError_t err = e->bf16 ? launch_gemm_bf16(a, am, ep, s) : launch_gemm_f32(a, am, ep, s);
+  if (err != hipSuccess) return fail(WF_E_HIP, "%s launch: %s", kClassNames[cls], hipGetErrorString(err));
+  return WF_OK;
+}
+
+int run_ln(wf_encoder *e, hipStream_t s, int cls, const float *x, const float *g, const float *b, void *out, int out_bf16, int M) {
+  const int d = e->cfg.d_model;
+  Scope sc(e, s, cls, 0.0, (double)M * d * (4 + (out_bf16 ? 2 : 4)));
+  hipError_t err = launch_layernorm(x, g, b, out, out_bf16, M, d, e->cfg.ln_eps, s);
+  if (err != hipSuccess) return fail(WF_E_HIP, "%s launch: %s", kClassNames[cls], hipGetErrorString(err));
+  return WF_OK;
+}
+
+// Attention work list: one item per (stream, block of q_tile queries), longest streams first so the
+// expensive items are scheduled before the cheap ones fill in.
+int build_work(const int32_t *cu_seqlens, int B, int q_tile, int32_t *work) {
+  std::vector<std::pair<int, int>> order(B);
+  for (int i = 0; i < B; ++i) order[i] = {cu_seqlens[i + 1] - cu_seqlens[i], i};
+  std::stable_sort(order.begin(), order.end(), [](const std::pair<int, int> &a, const std::pair<int, int> &b) { return a.first > b.first; });
+  int n = 0;
+  for (const auto &o : order)
+    for (int q0 = 0; q0 < o.first; q0 += q_tile) {
+      work[2 * n] = o.second;
+      work[2 * n + 1] = q0;
+      ++n;
+    }
+  return n;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// public ABI
+extern "C" {
+
+const char *wf_last_error(void) { return g_err; }
+
+int wf_config_check(const wf_config *cfg) { return check_config(cfg); }
+
+int wf_plan_batch(const wf_config *cfg, const int32_t *n_frames, int32_t B, int32_t *cu_seqlens, int64_t *total_frames,
+                  int64_t *total_tokens) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  Plan plan;
+  rc = plan_batch(*cfg, n_frames, B, nullptr, cu_seqlens, &plan);
+  if (rc) return rc;
+  if (total_frames) *total_frames = plan.total_frames;
+  if (total_tokens) *total_tokens = plan.total_tokens;
+  return WF_OK;
+}
+
+int wf_kernel_class_count(void) { return KC_COUNT; }
+
+void wf_encoder_destroy(wf_encoder *e) {
+  if (!e) return;
+  (void)hipSetDevice(e->device);
+  (void)hipDeviceSynchronize();
+  for (auto &r : e->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
+  for (auto ev : e->evt_pool) (void)hipEventDestroy(ev);
+  for (int i = 0; i < kStagingSlots; ++i) {
+    if (e->stage_host[i]) (void)hipHostFree(e->stage_host[i]);
+    if (e->stage_evt[i]) (void)hipEventDestroy(e->stage_evt[i]);
+  }
+  for (void *p : e->allocs) (void)hipFree(p);
+  delete e;
+}
+
+static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w) {
+  e->cfg = *cfg;
+  if (e->cfg.ln_eps <= 0.0f) e->cfg.ln_eps = 1e-5f;
+  e->bf16 = cfg->precision == WF_PRECISION_BF16;
+  e->es = e->bf16 ? 2 : 4;
+  HIP_TRY(hipGetDevice(&e->device));
+  HIP_TRY(init_kernels());
+  const int d = cfg->d_model, f = cfg->d_mlp, C = cfg->n_mels, H = cfg->hush_frames;
+  e->k1p = (int)round_up(3 * C, 64);
+  e->max_tokens = ((int64_t)cfg->max_total_frames + cfg->max_streams + 1) / 2;
+  e->max_pos = (cfg->max_frames_per_stream + 1) / 2;
+  e->max_work = e->max_tokens / attention_q_tile() + cfg->max_streams + 1;
+  int rc;
+
+  // ---- weights
+  if ((rc = upload_w(e, &e->conv1_w, conv_as_gemm_weight(w->conv1_w, d, C, e->k1p)))) return rc;
+  if ((rc = upload_w(e, &e->conv2_w, conv_as_gemm_weight(w->conv2_w, d, d, 3 * d)))) return rc;
+  if ((rc = upload_f32(e, &e->conv1_b, w->conv1_b, d))) return rc;
+  if ((rc = upload_f32(e, &e->conv2_b, w->conv2_b, d))) return rc;
+  if ((rc = upload_f32(e, &e->lnf_g, w->lnf_g, d))) return rc;
+  if ((rc = upload_f32(e, &e->lnf_b, w->lnf_b, d))) return rc;
+  {
+    std::vector<float> hm((size_t)std::max(H, 1) * C, 0.0f);
+    if (H > 0) memcpy(hm.data(), w->hush_mel, (size_t)H * C * 4);
+    if ((rc = upload_w(e, &e->hush, hm))) return rc;
+  }
+  {
+    // Sinusoidal table in double, rounded once to fp32.
+    const int half = d / 2;
+    std::vector<float> P((size_t)e->max_pos * d);
+    for (int c = 0; c < half; ++c) {
+      const double omega = std::exp(-std::log(10000.0) * (double)c / (double)(half - 1));
+      for (int64_t j = 0; j < e->max_pos; ++j) {
+        P[(size_t)j * d + c] = (float)std::sin((double)j * omega);
+        P[(size_t)j * d + half + c] = (float)std::cos((double)j * omega);
+      }
+    }
+    if ((rc = upload_f32(e, &e->pos, P.data(), P.size()))) return rc;
+  }
+  e->layers.resize(cfg->n_layers);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const wf_layer_weights &s = w->layers[l];
+    LayerDev &t = e->layers[l];
+    const float *req[] = {s.ln1_g, s.ln1_b, s.wq, s.bq, s.wk, s.wv, s.bv, s.wo, s.bo, s.ln2_g, s.ln2_b, s.w1, s.b1, s.w2, s.b2};
+    for (const float *p : req)
+      if (!p) return fail(WF_E_INVALID_ARG, "layer %d: a required weight pointer is NULL", l);
+    std::vector<float> wqkv((size_t)3 * d * d), bqkv((size_t)3 * d, 0.0f);
+    memcpy(wqkv.data(), s.wq, (size_t)d * d * 4);
+    memcpy(wqkv.data() + (size_t)d * d, s.wk, (size_t)d * d * 4);
+    memcpy(wqkv.data() + (size_t)2 * d * d, s.wv, (size_t)d * d * 4);
+    memcpy(bqkv.data(), s.bq, (size_t)d * 4);
+    if (s.bk) memcpy(bqkv.data() + d, s.bk, (size_t)d * 4);
+    memcpy(bqkv.data() + 2 * d, s.bv, (size_t)d * 4);
+    if ((rc = upload_w(e, &t.wqkv, wqkv))) return rc;
+    if ((rc = upload_f32(e, &t.bqkv, bqkv.data(), bqkv.size()))) return rc;
+    if ((rc = upload_w(e, &t.wo, std::vector<float>(s.wo, s.wo + (size_t)d * d)))) return rc;
+    if ((rc = upload_w(e, &t.w1, std::vector<float>(s.w1, s.w1 + (size_t)f * d)))) return rc;
+    if ((rc = upload_w(e, &t.w2, std::vector<float>(s.w2, s.w2 + (size_t)d * f)))) return rc;
+    if ((rc = upload_f32(e, &t.bo, s.bo, d))) return rc;
+    if ((rc = upload_f32(e, &t.b1, s.b1, f))) return rc;
+    if ((rc = upload_f32(e, &t.b2, s.b2, d))) return rc;
+    if ((rc = upload_f32(e, &t.ln1_g, s.ln1_g, d))) return rc;
+    if ((rc = upload_f32(e, &t.ln1_b, s.ln1_b, d))) return rc;
+    if ((rc = upload_f32(e, &t.ln2_g, s.ln2_g, d))) return rc;
+    if ((rc = upload_f32(e, &t.ln2_b, s.ln2_b, d))) return rc;
+  }
+
+  // ---- workspace
+  const int64_t F = cfg->max_total_frames, Mx = e->max_tokens;
+  if ((rc = dev_alloc(e, &e->packed, (size_t)F * C * e->es))) return rc;
+  if ((rc = dev_alloc(e, &e->G, (size_t)F * d * e->es))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->x, (size_t)Mx * d * 4))) return rc;
+  if ((rc = dev_alloc(e, &e->u, (size_t)Mx * d * e->es))) return rc;
+  if ((rc = dev_alloc(e, &e->qkv, (size_t)Mx * 3 * d * e->es))) return rc;
+  if ((rc = dev_alloc(e, &e->h, (size_t)Mx * f * e->es))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->frame_src, (size_t)F * 4))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->frame_flags, (size_t)F * 4))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->tok_src, (size_t)Mx * 4))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->tok_flags, (size_t)Mx * 4))) return rc;
+  if ((rc = dev_alloc(e, (void **)&e->tok_pos, (size_t)Mx * 4))) return rc;
+  e->idx_ints = 4 * ((int64_t)cfg->max_streams + 1) + 2 * e->max_work;
+  if ((rc = dev_alloc(e, (void **)&e->idx_dev, (size_t)e->idx_ints * 4))) return rc;
+  for (int i = 0; i < kStagingSlots; ++i) {
+    HIP_TRY(hipHostMalloc((void **)&e->stage_host[i], (size_t)e->idx_ints * 4, hipHostMallocDefault));
+    HIP_TRY(hipEventCreateWithFlags(&e->stage_evt[i], hipEventDisableTiming));
+  }
+  HIP_TRY(hipDeviceSynchronize());
+  return WF_OK;
+}
+
+int wf_encoder_create(const wf_config *cfg, const wf_weights *w, wf_encoder **out) {
+  if (!out) return fail(WF_E_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!w) return fail(WF_E_INVALID_ARG, "weights is NULL");
+  if (!w->conv1_w || !w->conv1_b || !w->conv2_w || !w->conv2_b || !w->lnf_g || !w->lnf_b)
+    return fail(WF_E_INVALID_ARG, "a stem or final-LayerNorm weight pointer is NULL");
+  if (cfg->hush_frames > 0 && !w->hush_mel) return fail(WF_E_INVALID_ARG, "hush_mel is NULL but hush_frames = %d", cfg->hush_frames);
+  if (cfg->n_layers > 0 && !w->layers) return fail(WF_E_INVALID_ARG, "layers is NULL but n_layers = %d", cfg->n_layers);
+  wf_encoder *e = new (std::nothrow) wf_encoder();
+  if (!e) return fail(WF_E_OOM, "host allocation failed");
+  rc = create_impl(e, cfg, w);
+  if (rc) {
+    char keep[sizeof(g_err)];
+    memcpy(keep, g_err, sizeof(keep));
+    wf_encoder_destroy(e);
+    memcpy(g_err, keep, sizeof(keep));
+    return rc;
+  }
+  *out = e;
+  return WF_OK;
+}
+
+int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const int32_t *frame_offset, const int32_t *n_frames,
+                    int32_t B, void *out_dev, int32_t out_dtype, int64_t out_capacity_tokens, int32_t *cu_seqlens_host,
+                    void *hip_stream) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  if (!mel_dev || !out_dev || !frame_offset) return fail(WF_E_INVALID_ARG, "mel_dev, out_dev or frame_offset is NULL");
+  if (mel_dtype != WF_DTYPE_F32 && mel_dtype != WF_DTYPE_BF16) return fail(WF_E_INVALID_ARG, "mel_dtype = %d", mel_dtype);
+  if (out_dtype != WF_DTYPE_F32 && out_dtype != WF_DTYPE_BF16) return fail(WF_E_INVALID_ARG, "out_dtype = %d", out_dtype);
+  const wf_config &c = e->cfg;
+  if (B >= 1 && B <= c.max_streams)
+    for (int i = 0; i < B; ++i)
+      if (frame_offset[i] < 0) return fail(WF_E_INVALID_ARG, "frame_offset[%d] = %d is negative", i, frame_offset[i]);
+
+  // ---- plan on the host, into the next pinned staging slot
+  const int slot = e->stage_next;
+  int32_t *hs = e->stage_host[slot];
+  if (e->stage_used[slot]) HIP_TRY(hipEventSynchronize(e->stage_evt[slot]));   // its previous copy has left the buffer
+  const int S1 = c.max_streams + 1;
+  int32_t *h_cu_frames = hs, *h_cu_seq = hs + S1, *h_off = hs + 2 * S1, *h_nf = hs + 3 * S1, *h_work = hs + 4 * S1;
+  Plan plan;
+  int rc = plan_batch(c, n_frames, B, h_cu_frames, h_cu_seq, &plan);
+  if (rc) return rc;
+  const int M = (int)plan.total_tokens, TF = (int)plan.total_frames;
+  if (M > out_capacity_tokens)
+    return fail(WF_E_CAPACITY, "batch produces %d tokens but out_capacity_tokens = %lld", M, (long long)out_capacity_tokens);
+  memcpy(h_off, frame_offset, (size_t)B * 4);
+  memcpy(h_nf, n_frames, (size_t)B * 4);
+  const int n_work = build_work(h_cu_seq, B, attention_q_tile(), h_work);
+  if (cu_seqlens_host) memcpy(cu_seqlens_host, h_cu_seq, (size_t)(B + 1) * 4);
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  const size_t idx_bytes = (size_t)(4 * S1 + 2 * n_work) * 4;
+  HIP_TRY(hipMemcpyAsync(e->idx_dev, hs, idx_bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipEventRecord(e->stage_evt[slot], s));
+  e->stage_used[slot] = true;
+  e->stage_next = (slot + 1) % kStagingSlots;
+  const int32_t *d_cu_frames = e->idx_dev, *d_cu_seq = e->idx_dev + S1, *d_off = e->idx_dev + 2 * S1, *d_nf = e->idx_dev + 3 * S1,
+                *d_work = e->idx_dev + 4 * S1;
+
+  const int d = c.d_model, f = c.d_mlp, C = c.n_mels;
+  const int act_bf16 = e->bf16 ? 1 : 0;
+  const int es = e->es;
+
+  // ---- a0: pack + hush append + row maps
+  {
+    PrepArgs a{};
+    a.mel = mel_dev; a.hush = e->hush; a.packed = e->packed;
+    a.cu_frames = d_cu_frames; a.cu_seqlens = d_cu_seq; a.frame_offset = d_off; a.n_frames = d_nf;
+    a.frame_src = e->frame_src; a.frame_flags = e->frame_flags;
+    a.tok_src = e->tok_src; a.tok_flags = e->tok_flags; a.tok_pos = e->tok_pos;
+    a.B = B; a.n_mels = C; a.total_frames = TF; a.M = M; a.mel_is_bf16 = mel_dtype == WF_DTYPE_BF16;
+    Scope sc(e, s, KC_PREP, 0.0, (double)TF * C * ((mel_dtype == WF_DTYPE_BF16 ? 2 : 4) + es) + 8.0 * TF + 12.0 * M);
+    hipError_t err = launch_prep(a, act_bf16, s);
+    if (err != hipSuccess) return fail(WF_E_HIP, "prep launch: %s", hipGetErrorString(err));
+  }
+  // ---- a1: conv1 + GELU as a GEMM over 3-frame windows
+  {
+    GemmArgs a{};
+    a.A = e->packed; a.W = e->conv1_w; a.bias = e->conv1_b; a.out = e->G;
+    a.M = TF; a.N = d; a.K = e->k1p; a.lda = C; a.ldo = d;
+    a.row_src = e->frame_src; a.row_flags = e->frame_flags; a.C = C;
+    if ((rc = run_gemm(e, s, KC_CONV1, a, A_CONV3, EPI_BIAS_GELU, 3 * C, es, TF, C))) return rc;
+  }
+  // ---- a2: conv2 (stride 2) + GELU + positions -> fp32 residual stream
+  {
+    GemmArgs a{};
+    a.A = e->G; a.W = e->conv2_w; a.bias = e->conv2_b; a.out = e->x;
+    a.M = M; a.N = d; a.K = 3 * d; a.lda = d; a.ldo = d;
+    a.row_src = e->tok_src; a.row_flags = e->tok_flags; a.C = d;
+    a.pos = e->pos; a.row_pos = e->tok_pos;
+    if ((rc = run_gemm(e, s, KC_CONV2, a, A_CONV3, EPI_BIAS_GELU_POS, 3 * d, 4, TF, d))) return rc;
+  }
+  // ---- transformer blocks
+  double attn_flops = 0.0;
+  for (int i = 0; i < B; ++i) {
+    const double L = h_cu_seq[i + 1] - h_cu_seq[i];
+    attn_flops += 4.0 * L * L * d;
+  }
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerDev &w = e->layers[l];
+    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln1_g, w.ln1_b, e->u, act_bf16, M))) return rc;
+    {
+      GemmArgs a{};
+      a.A = e->u; a.W = w.wqkv; a.bias = w.bqkv; a.out = e->qkv;
+      a.M = M; a.N = 3 * d; a.K = d; a.lda = d; a.ldo = 3 * d;
+      if ((rc = run_gemm(e, s, KC_QKV, a, A_PLAIN, EPI_BIAS, d, es, M, d))) return rc;
+    }
+    {
+      AttnArgs a{};
+      a.qkv = e->qkv; a.out = e->u; a.cu_seqlens = d_cu_seq; a.work = d_work;
+      a.n_work = n_work; a.n_heads = c.n_heads; a.d_model = d; a.B = B; a.M = M;
+      a.scale = 0.125f;
+      Scope sc(e, s, KC_ATTN, attn_flops, (double)M * 4 * d * es);
+      hipError_t err = e->bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s);
+      if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
+    }
+    {
+      GemmArgs a{};
+      a.A = e->u; a.W = w.wo; a.bias = w.bo; a.out = e->x;
+      a.M = M; a.N = d; a.K = d; a.lda = d; a.ldo = d;
+      if ((rc = run_gemm(e, s, KC_OUT, a, A_PLAIN, EPI_BIAS_RESID, d, 4, M, d))) return rc;
+    }
+    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln2_g, w.ln2_b, e->u, act_bf16, M))) return rc;
+    {
+      GemmArgs a{};
+      a.A = e->u; a.W = w.w1; a.bias = w.b1; a.out = e->h;
+      a.M = M; a.N = f; a.K = d; a.lda = d; a.ldo = f;
+      if ((rc = run_gemm(e, s, KC_FC1, a, A_PLAIN, EPI_BIAS_GELU, d, es, M, d))) return rc;
+    }
+    {
+      GemmArgs a{};
+      a.A = e->h; a.W = w.w2; a.bias = w.b2; a.out = e->x;
+      a.M = M; a.N = d; a.K = f; a.lda = f; a.ldo = d;
+      if ((rc = run_gemm(e, s, KC_FC2, a, A_PLAIN, EPI_BIAS_RESID, f, 4, M, f))) return rc;
+    }
+  }
+  // ---- a9: final LayerNorm straight into the caller's buffer
+  if ((rc = run_ln(e, s, KC_LNF, e->x, e->lnf_g, e->lnf_b, out_dev, out_dtype == WF_DTYPE_BF16, M))) return rc;
+  return WF_OK;
+}
+
+int wf_encoder_set_profiling(wf_encoder *e, int32_t enabled) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  e->profiling = enabled != 0;
+  return WF_OK;
+}
+
+int wf_encoder_kernel_stats(wf_encoder *e, wf_kernel_stat *stats, int32_t n_stats) {
+  if (!e || !stats) return fail(WF_E_INVALID_ARG, "encoder or stats is NULL");
+  if (n_stats < KC_COUNT) return fail(WF_E_INVALID_ARG, "n_stats = %d, need %d", n_stats, (int)KC_COUNT);
+  for (int i = 0; i < KC_COUNT; ++i) stats[i] = wf_kernel_stat{kClassNames[i], 0, 0.0, 0.0, 0.0};
+  for (auto &r : e->prof) {
+    HIP_TRY(hipEventSynchronize(r.t1));
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.t0, r.t1));
+    wf_kernel_stat &st = stats[r.cls];
+    st.launches += 1; st.total_ms += ms; st.flops += r.flops; st.bytes += r.bytes;
+    e->evt_pool.push_back(r.t0);
+    e->evt_pool.push_back(r.t1);
+  }
+  e->prof.clear();
+  return WF_OK;
+}
+
+// ---- operator-level entry points -------------------------------------------------------------
+int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const float *bias_dev, void *out_dev, int32_t M,
+                 int32_t N, int32_t K, int32_t epilogue, void *hip_stream) {
+  if (!a_dev || !w_dev || !bias_dev || !out_dev) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (M < 1 || N < 128 || N % 128 || K < 64 || K % 64) return fail(WF_E_INVALID_ARG, "need M >= 1, N %% 128 == 0, K %% 64 == 0");
+  if (epilogue < 0 || epilogue > 2) return fail(WF_E_INVALID_ARG, "epilogue = %d", epilogue);
+  GemmArgs a{};
+  a.A = a_dev; a.W = w_dev; a.bias = bias_dev; a.out = out_dev;
+  a.M = M; a.N = N; a.K = K; a.lda = K; a.ldo = N;
+  hipError_t err = precision == WF_PRECISION_BF16 ? launch_gemm_bf16(a, A_PLAIN, (Epilogue)epilogue, (hipStream_t)hip_stream)
+                                                  : launch_gemm_f32(a, A_PLAIN, (Epilogue)epilogue, (hipStream_t)hip_stream);
+  if (err != hipSuccess) return fail(WF_E_HIP, "linear launch: %s", hipGetErrorString(err));
+  return WF_OK;
+}
+
+int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, void *out_dev, int32_t out_dtype, int32_t M,
+                    int32_t d, float eps, void *hip_stream) {
+  if (!x_dev || !g_dev || !b_dev || !out_dev) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (M < 1 || d < 4 || d % 4 || d > 2048) return fail(WF_E_INVALID_ARG, "need M >= 1, d %% 4 == 0, d <= 2048");
+  hipError_t err = launch_layernorm(x_dev, g_dev, b_dev, out_dev, out_dtype == WF_DTYPE_BF16, M, d, eps, (hipStream_t)hip_stream);
+  if (err != hipSuccess) return fail(WF_E_HIP, "layernorm launch: %s", hipGetErrorString(err));
+  return WF_OK;
+}
+
+int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
+                    int32_t n_heads, void *hip_stream) {
+  if (!qkv_dev || !out_dev || !cu_seqlens_host) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (B < 1 || n_heads < 1 || cu_seqlens_host[0] != 0) return fail(WF_E_INVALID_ARG, "need B >= 1, n_heads >= 1, cu_seqlens[0] == 0");
+  for (int i = 0; i < B; ++i)
+    if (cu_seqlens_host[i + 1] <= cu_seqlens_host[i]) return fail(WF_E_INVALID_ARG, "stream %d is empty", i);
+  const int M = cu_seqlens_host[B];
+  const int qt = attention_q_tile();
+  std::vector<int32_t> idx((size_t)(B + 1) + 2 * ((size_t)M / qt + B + 1));
+  memcpy(idx.data(), cu_seqlens_host, (size_t)(B + 1) * 4);
+  const int n_work = build_work(cu_seqlens_host, B, qt, idx.data() + B + 1);
+  int32_t *d_idx = nullptr;
+  HIP_TRY(hipMalloc((void **)&d_idx, idx.size() * 4));
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t err = hipMemcpyAsync(d_idx, idx.data(), idx.size() * 4, hipMemcpyHostToDevice, s);
+  if (err == hipSuccess) {
+    AttnArgs a{};
+    a.qkv = qkv_dev; a.out = out_dev; a.cu_seqlens = d_idx; a.work = d_idx + B + 1;
+    a.n_work = n_work; a.n_heads = n_heads; a.d_model = n_heads * 64; a.B = B; a.M = M; a.scale = 0.125f;
+    err = precision == WF_PRECISION_BF16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s);
+  }
+  hipError_t err2 = hipStreamSynchronize(s);
+  (void)hipFree(d_idx);
+  if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
+  if (err2 != hipSuccess) return fail(WF_E_HIP, "attention: %s", hipGetErrorString(err2));
+  return WF_OK;
+}
+
+}  // extern "C"
+
+namespace wf {
+hipError_t init_kernels() { return hipSuccess; }
+}  // namespace wf

@@ -1,0 +1,235 @@
+// bf16 MFMA GEMM for gfx950:  out = epilogue(A . W^T),  A [M, K] activations, W [N, K] weights,
+// fp32 accumulation.  Used for the QKV / out / fc1 / fc2 projections and, with a gathered A
+// operand, for both convolutions of the stem (a width-3 convolution over a packed time-major
+// matrix is a GEMM whose A row is the contiguous window of three frames).
+//
+// Tiling: one workgroup computes a BM x BN tile; the K loop advances 64 elements at a time through
+// two LDS stages (global -> registers -> LDS, one barrier per step).  Each wave owns a
+// (BM/WM) x (BN/WN) sub-tile built from v_mfma_f32_32x32x16_bf16.  The weight fragment is the MFMA's
+// first operand and the activation fragment the second, so a lane ends up holding four consecutive
+// output features of one token and the epilogue can store 8 or 16 contiguous bytes per lane.
+// LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row & 7) so that both
+// the row-per-lane fragment reads and the tile writes spread over all banks.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace wf {
+
+namespace {
+
+constexpr int BK = 64;
+
+template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int IM = TM / 32, IN = TN / 32;
+  constexpr int XCH = BM * 8 / NT;   // 16-byte chunks of the activation tile per thread
+  constexpr int WCH = BN * 8 / NT;
+  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char *sX = smem;                        // [2][BM][128 B]
+  unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
+
+  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own L2), so
+  // give every XCD a contiguous run of tiles: tiles that share activation rows then share an L2.
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int tiles_n = p.N / BN;
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= n_tiles) return;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, lg = lane >> 5;
+
+  // ---- per-thread load descriptors (fixed over the K loop) ----
+  const __bf16 *A = (const __bf16 *)p.A;
+  const __bf16 *W = (const __bf16 *)p.W;
+  const __bf16 *xptr[XCH];
+  int xflags[XCH];
+  int xlds[XCH];
+#pragma unroll
+  for (int i = 0; i < XCH; ++i) {
+    const int c = i * NT + tid;
+    const int r = c >> 3, ch = c & 7;
+    int row = m0 + r;
+    row = row < p.M ? row : p.M - 1;              // rows past M are computed but never stored
+    if (AMODE == A_PLAIN) {
+      xptr[i] = A + (size_t)row * p.lda + ch * 8;
+      xflags[i] = 0;
+    } else {
+      xptr[i] = A + (long)p.row_src[row] * p.C + ch * 8;
+      xflags[i] = p.row_flags[row];
+    }
+    xlds[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+  }
+  const __bf16 *wptr[WCH];
+  int wlds[WCH];
+#pragma unroll
+  for (int i = 0; i < WCH; ++i) {
+    const int c = i * NT + tid;
+    const int r = c >> 3, ch = c & 7;
+    wptr[i] = W + (size_t)(n0 + r) * p.K + ch * 8;
+    wlds[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+  }
+
+  uint4 xr[XCH], wr[WCH];
+  auto load_tile = [&](int kt) {
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+      if (AMODE == A_PLAIN) {
+        xr[i] = *(const uint4 *)(xptr[i] + k0);
+      } else {
+        const int kk = k0 + ((i * NT + tid) & 7) * 8;   // chunks never straddle taps: C % 8 == 0
+        const int tap = kk / p.C;
+        const bool ok = (kk < 3 * p.C) && !((tap == 0) && (xflags[i] & 1)) && !((tap == 2) && (xflags[i] & 2));
+        xr[i] = ok ? *(const uint4 *)(xptr[i] + k0) : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) wr[i] = *(const uint4 *)(wptr[i] + k0);
+  };
+  auto store_tile = [&](int stage) {
+    unsigned char *dx = sX + stage * BM * 128;
+    unsigned char *dw = sW + stage * BN * 128;
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) *(uint4 *)(dx + xlds[i]) = xr[i];
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) *(uint4 *)(dw + wlds[i]) = wr[i];
+  };
+
+  f32x16 acc[IM][IN];
+#pragma unroll
+  for (int i = 0; i < IM; ++i)
+#pragma unroll
+    for (int j = 0; j < IN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int nk = p.K / BK;
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  // fragment read offsets: lane reads row (l32) of a 32-row group, chunk 2*ks + lg (swizzled)
+  const int xrow0 = (wm * TM + l32) * 128;
+  const int wrow0 = (wn * TN + l32) * 128;
+  const int sw = l32 & 7;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < nk) load_tile(kt + 1);
+    const unsigned char *cx = sX + stage * BM * 128 + xrow0;
+    const unsigned char *cw = sW + stage * BN * 128 + wrow0;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int choff = ((2 * ks + lg) ^ sw) << 4;
+      bf16x8 wf[IN], xf[IM];
+#pragma unroll
+      for (int j = 0; j < IN; ++j) wf[j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
+#pragma unroll
+      for (int i = 0; i < IM; ++i) xf[i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
+#pragma unroll
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < IN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_tile(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds, per 32x32 block, token m = l32 and features 8*g + 4*lg + (0..3), g = 0..3
+#pragma unroll
+  for (int i = 0; i < IM; ++i) {
+    const int m = m0 + wm * TM + i * 32 + l32;
+    if (m >= p.M) continue;
+    int prow = 0;
+    if (EPI == EPI_BIAS_GELU_POS) prow = p.row_pos[m];
+#pragma unroll
+    for (int j = 0; j < IN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn * TN + j * 32 + g * 8 + lg * 4;
+        const f32x4 b = *(const f32x4 *)(p.bias + n);
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
+        if (EPI == EPI_BIAS) {
+          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
+        } else if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
+          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
+        } else if (EPI == EPI_BIAS_RESID) {
+          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + n);
+          const f32x4 x = *o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += x[e];
+          *o = v;
+        } else {
+          const f32x4 pe = *(const f32x4 *)(p.pos + (size_t)prow * p.N + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]) + pe[e];
+          *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + n) = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
+hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
+  constexpr int smem = 2 * (BM + BN) * 128;
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, AMODE, EPI>;
+  static bool attr_set = false;   // set once per process; device-wide limit, idempotent
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
+  const int grid = ((tiles + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  return hipGetLastError();
+}
+
+template <int AMODE, int EPI>
+hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
+  // Large tile when it divides N and there is enough work to fill 256 CUs with it.
+  const bool big = (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
+  if (big) return launch_cfg<256, 256, 2, 4, AMODE, EPI>(a, s);
+  return launch_cfg<128, 128, 2, 2, AMODE, EPI>(a, s);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
+  if (a.M <= 0) return hipSuccess;
+  if (a.N % 128 != 0 || a.K % BK != 0 || a.K <= 0) return hipErrorInvalidValue;
+  if (amode == A_PLAIN) {
+    if (a.lda % 8 != 0) return hipErrorInvalidValue;
+    switch (epi) {
+      case EPI_BIAS: return launch_shape<A_PLAIN, EPI_BIAS>(a, s);
+      case EPI_BIAS_GELU: return launch_shape<A_PLAIN, EPI_BIAS_GELU>(a, s);
+      case EPI_BIAS_RESID: return launch_shape<A_PLAIN, EPI_BIAS_RESID>(a, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  if (a.C % 8 != 0 || 3 * a.C > a.K) return hipErrorInvalidValue;
+  switch (epi) {
+    case EPI_BIAS_GELU: return launch_shape<A_CONV3, EPI_BIAS_GELU>(a, s);
+    case EPI_BIAS_GELU_POS: return launch_shape<A_CONV3, EPI_BIAS_GELU_POS>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace wf

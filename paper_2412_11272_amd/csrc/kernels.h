@@ -1,0 +1,77 @@
+// Internal launcher interface between the host runtime (encoder.hip) and the gfx950 kernels.
+// Nothing here is part of the public ABI (include/wf_encoder.h is).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wf {
+
+typedef uint16_t bf16_raw;   // storage type of a bfloat16 value in host-visible structs
+
+// How the GEMM reads its activation operand.
+enum AMode : int {
+  A_PLAIN = 0,   // row r of the operand is A + r * lda
+  A_CONV3 = 1,   // row r is a contiguous window of 3*C elements starting at row_src[r] * C of a
+                 // [rows, C] matrix: the three taps of a width-3 convolution.  row_flags[r] bit 0
+                 // zeroes tap 0 (first frame of a stream), bit 1 zeroes tap 2 (last frame).
+};
+
+// What the GEMM does with acc = A . W^T.
+enum Epilogue : int {
+  EPI_BIAS = 0,            // out = acc + bias                          (QKV projection)
+  EPI_BIAS_GELU = 1,       // out = GELU(acc + bias)                    (fc1, first convolution)
+  EPI_BIAS_RESID = 2,      // out(fp32) += acc + bias, in place         (out-projection, fc2)
+  EPI_BIAS_GELU_POS = 3,   // out(fp32) = GELU(acc + bias) + pos[row_pos[r]]   (second convolution)
+};
+
+struct GemmArgs {
+  const void *A;            // activations: bf16 (MFMA path) or fp32 (debug path)
+  const void *W;            // weights [N, K] row-major, same element type as A; K zero-padded
+  const float *bias;        // [N]
+  void *out;                // [M, ldo]; bf16 for EPI_BIAS / EPI_BIAS_GELU on the MFMA path, else fp32
+  int32_t M, N, K;          // K is the padded reduction length (multiple of 64 on the MFMA path)
+  int32_t lda, ldo;
+  // A_CONV3 only
+  const int32_t *row_src;
+  const int32_t *row_flags;
+  int32_t C;                // channels per tap; 3*C <= K, elements at k >= 3*C read as zero
+  // EPI_BIAS_GELU_POS only
+  const float *pos;         // [n_pos, N]
+  const int32_t *row_pos;   // [M]
+};
+
+struct AttnArgs {
+  const void *qkv;          // [M, 3*d]: q | k | v, head h owns columns [64h, 64h+64) of each third
+  void *out;                // [M, d]
+  const int32_t *cu_seqlens;// [B+1]
+  const int32_t *work;      // [n_work][2]: (stream, first query row inside the stream), longest first
+  int32_t n_work, n_heads, d_model, B, M;
+  float scale;              // 1/sqrt(64)
+};
+
+struct PrepArgs {
+  const void *mel;          // caller's frames [*, n_mels]
+  const void *hush;         // [H, n_mels] same dtype as the packed output
+  void *packed;             // [total_frames, n_mels]
+  const int32_t *cu_frames, *cu_seqlens, *frame_offset, *n_frames;
+  int32_t *frame_src, *frame_flags;            // [total_frames]  conv1 row map
+  int32_t *tok_src, *tok_flags, *tok_pos;      // [M]             conv2 row map + position index
+  int32_t B, n_mels, total_frames, M, mel_is_bf16;
+};
+
+// bf16 MFMA path -------------------------------------------------------------------------------
+hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);
+hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
+hipError_t launch_layernorm(const float *x, const float *g, const float *b, void *out, int out_bf16,
+                            int32_t M, int32_t d, float eps, hipStream_t s);
+hipError_t launch_prep(const PrepArgs &a, int packed_bf16, hipStream_t s);
+int attention_q_tile();     // query rows per attention work item
+
+// fp32 debug path ------------------------------------------------------------------------------
+hipError_t launch_gemm_f32(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);
+hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t s);
+
+// one-time per-process kernel attribute setup (dynamic LDS limits)
+hipError_t init_kernels();
+
+}  // namespace wf

@@ -1,0 +1,105 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its
+host-side validation and ragged-batch planner behave as documented.  No compute call is made."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2412_11272_amd import binding as wf
+from paper_2412_11272_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**kw):
+    base = dict(n_mels=80, d_model=384, n_layers=4, n_heads=6, d_mlp=1536, hush_frames=50, max_streams=4,
+                max_total_frames=4000, max_frames_per_stream=3050, precision=0, ln_eps=1e-5)
+    base.update(kw)
+    return wf.WfConfig(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "wf_encoder.h")).read()
+    declared = set(re.findall(r"\b(wf_[a-z_0-9]+)\s*\(", header))
+    assert {"wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy"} <= declared
+    L = wf.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in the header but not exported"
+    assert declared == set(wf.EXPORTS)
+
+
+def test_config_struct_layout_matches_header():
+    assert C.sizeof(wf.WfConfig) == 11 * 4
+    assert C.sizeof(wf.WfLayerWeights) == 16 * C.sizeof(C.c_void_p)
+    assert C.sizeof(wf.WfWeights) == 8 * C.sizeof(C.c_void_p)
+
+
+def test_config_check():
+    assert wf.config_check(_cfg()) == wf.WF_OK
+    for bad in (dict(n_heads=5), dict(d_model=100, n_heads=1), dict(n_mels=81), dict(d_mlp=100), dict(n_layers=-1),
+                dict(hush_frames=-1), dict(max_streams=0), dict(max_frames_per_stream=50), dict(precision=7),
+                dict(max_total_frames=100)):
+        assert wf.config_check(_cfg(**bad)) == wf.WF_E_INVALID_ARG, bad
+        assert wf.last_error() != ""
+    for shape in synth.SHAPES.values():
+        cfg = wf.make_config(shape, 50, 64, 200000, 3050)
+        assert wf.config_check(cfg) == wf.WF_OK
+
+
+def test_plan_batch_prefix_sums_and_paper_shape_facts():
+    cfg = _cfg(max_streams=8, max_total_frames=20000)
+    cu, tf, tt = wf.plan_batch(cfg, [100, 3000, 1, 2, 1450])
+    lens = [(t + 50 + 1) // 2 for t in (100, 3000, 1, 2, 1450)]
+    assert lens == [75, 1525, 26, 26, 750]        # 1 s + hush -> 75; 30 s + hush -> 1525; 15 s incl. hush -> 750
+    assert cu.tolist() == [0] + np.cumsum(lens).tolist()
+    assert tf == sum(t + 50 for t in (100, 3000, 1, 2, 1450)) and tt == sum(lens)
+    cfg0 = _cfg(hush_frames=0, max_frames_per_stream=3000)
+    cu, tf, tt = wf.plan_batch(cfg0, [3000, 50])
+    assert cu.tolist() == [0, 1500, 1525]          # 30 s -> 1500 tokens, 0.5 s -> 25 tokens
+
+
+def test_plan_batch_errors():
+    cfg = _cfg()
+    with pytest.raises(wf.WfError) as e:
+        wf.plan_batch(cfg, [100, 0])
+    assert e.value.code == wf.WF_E_INVALID_ARG
+    with pytest.raises(wf.WfError) as e:
+        wf.plan_batch(cfg, [])
+    assert e.value.code == wf.WF_E_INVALID_ARG
+    with pytest.raises(wf.WfError) as e:
+        wf.plan_batch(cfg, [10] * 5)
+    assert e.value.code == wf.WF_E_CAPACITY
+    with pytest.raises(wf.WfError) as e:
+        wf.plan_batch(cfg, [3001])
+    assert e.value.code == wf.WF_E_CAPACITY and "max_frames_per_stream" in str(e.value)
+    with pytest.raises(wf.WfError) as e:
+        wf.plan_batch(cfg, [2000, 2000])
+    assert e.value.code == wf.WF_E_CAPACITY and "max_total_frames" in str(e.value)
+    assert wf.lib().wf_plan_batch(None, None, 1, None, None, None) == wf.WF_E_INVALID_ARG
+
+
+def test_null_arguments_are_rejected_without_a_gpu():
+    L = wf.lib()
+    assert L.wf_encoder_create(None, None, None) == wf.WF_E_INVALID_ARG
+    h = C.c_void_p(None)
+    cfg = _cfg()
+    assert L.wf_encoder_create(C.byref(cfg), None, C.byref(h)) == wf.WF_E_INVALID_ARG and not h
+    assert L.wf_encode_batch(None, None, 0, None, None, 1, None, 0, 0, None, None) == wf.WF_E_INVALID_ARG
+    L.wf_encoder_destroy(None)                      # NULL-safe
+    assert L.wf_kernel_class_count() >= 8
+
+
+def test_workload_recipes():
+    wl = synth.workload("cfg5")
+    assert len(wl.n_frames) == 64 and min(wl.n_frames) >= 100 and max(wl.n_frames) <= 3000
+    assert synth.workload("cfg5").n_frames == wl.n_frames            # seeded
+    wl3 = synth.workload("cfg3")
+    assert len(wl3.n_frames) == 16 and min(wl3.n_frames) >= 100 and max(wl3.n_frames) <= 1000
+    w, hush, mels = synth.materialize(synth.workload("cfg1"))
+    assert hush.shape == (50, 80) and mels[0].shape == (100, 80)
+    assert mels[0].min() >= -1 and mels[0].max() <= 1 and abs(mels[0].mean() + 0.3) < 0.05
+    assert abs(w["layers"][0]["wq"].std() - 0.02) < 1e-3 and w["layers"][0]["bk"] is None
+    w4, h4, m4 = synth.materialize(synth.workload("cfg4a"))
+    assert m4[0].shape == (3000, 80) and np.all(m4[0][600:] == -1.0) and len(h4) == 0

@@ -1,0 +1,125 @@
+"""Per-operator parity on the GPU, through the C ABI: each kernel family against the matching step
+of the oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle import encoder_oracle as O
+from paper_2412_11272_amd import binding as wf
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_round(a: np.ndarray):
+    import torch
+    return torch.from_numpy(a.astype(np.float32)).bfloat16()
+
+
+def _rel(got, ref):
+    return float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+
+
+# M spans: one partial small tile, several small tiles + ragged tail, and enough rows for the large tile
+@pytest.mark.parametrize("M,N,K", [(75, 384, 384), (300, 1152, 384), (1000, 128, 1536), (257, 256, 64),
+                                   (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280)])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_linear_bf16(M, N, K, epi):
+    import torch
+    if epi != 0 and M > 1000 and N == 3840:
+        pytest.skip("covered by the other large shapes")
+    rng = np.random.default_rng(M + N + K + epi)
+    a = _bf16_round(rng.standard_normal((M, K)))
+    w = _bf16_round(rng.standard_normal((N, K)) * 0.05)
+    bias = rng.standard_normal(N).astype(np.float32)
+    a64, w64 = a.float().numpy().astype(np.float64), w.float().numpy().astype(np.float64)
+    ref = O.linear(a64, w64, bias.astype(np.float64))
+    ad, wd, bd = a.cuda(), w.cuda(), torch.from_numpy(bias).cuda()
+    if epi == 2:
+        x0 = rng.standard_normal((M, N)).astype(np.float32)
+        out = torch.from_numpy(x0).cuda()
+        ref = x0.astype(np.float64) + ref
+    else:
+        out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        if epi == 1:
+            ref = O.gelu(ref)
+    wf.op_linear(wf.WF_PRECISION_BF16, ad, wd, bd, out, epi)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    # inputs are exactly representable, accumulation is fp32: only the output rounding (2^-9) remains
+    tol = 5e-3 if epi != 2 else 2e-5
+    assert _rel(got, ref) < tol
+
+
+@pytest.mark.parametrize("M,N,K", [(75, 384, 384), (300, 1152, 240), (1000, 128, 1536)])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_linear_f32(M, N, K, epi):
+    import torch
+    if K % 64:
+        K = 256
+    rng = np.random.default_rng(M + N + K + epi)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    ref = O.linear(a.astype(np.float64), w.astype(np.float64), bias.astype(np.float64))
+    x0 = rng.standard_normal((M, N)).astype(np.float32)
+    out = torch.from_numpy(x0.copy()).cuda()
+    if epi == 1:
+        ref = O.gelu(ref)
+    if epi == 2:
+        ref = x0 + ref
+    wf.op_linear(wf.WF_PRECISION_F32, torch.from_numpy(a).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(bias).cuda(),
+                 out, epi)
+    torch.cuda.synchronize()
+    assert _rel(out.cpu().numpy(), ref) < 2e-6
+
+
+@pytest.mark.parametrize("M,d", [(1, 128), (75, 384), (333, 512), (1001, 768), (50, 1024), (4097, 1280), (3, 2048)])
+def test_layernorm(M, d):
+    import torch
+    rng = np.random.default_rng(M * d)
+    x = (rng.standard_normal((M, d)) * 3 + 0.7).astype(np.float32)
+    x[0] = 2.5                                               # constant row -> exactly the shift
+    g = rng.standard_normal(d).astype(np.float32)
+    b = rng.standard_normal(d).astype(np.float32)
+    ref = O.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    xd, gd, bd = (torch.from_numpy(t).cuda() for t in (x, g, b))
+    out = torch.empty((M, d), dtype=torch.float32, device="cuda")
+    wf.op_layernorm(xd, gd, bd, out)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), ref, atol=2e-5)
+    outb = torch.empty((M, d), dtype=torch.bfloat16, device="cuda")
+    wf.op_layernorm(xd, gd, bd, outb)
+    torch.cuda.synchronize()
+    assert _rel(outb.float().cpu().numpy(), ref) < 5e-3
+
+
+LENS = [[1], [75], [64, 65, 63], [128, 129, 1, 2, 300], [1525, 75, 700]]
+
+
+@pytest.mark.parametrize("lens", LENS)
+@pytest.mark.parametrize("sharp", [1.0, 6.0])
+@pytest.mark.parametrize("precision", [wf.WF_PRECISION_BF16, wf.WF_PRECISION_F32])
+def test_attention(lens, sharp, precision):
+    import torch
+    n_heads = 3
+    d = 64 * n_heads
+    M = sum(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rng = np.random.default_rng(M + int(sharp))
+    qkv = rng.standard_normal((M, 3 * d)).astype(np.float32)
+    qkv[:, :2 * d] *= np.sqrt(sharp)                         # logits std ~ sharp
+    if precision == wf.WF_PRECISION_BF16:
+        t = torch.from_numpy(qkv).bfloat16()
+        qkv64 = t.float().numpy().astype(np.float64)
+        out = torch.full((M, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    else:
+        t = torch.from_numpy(qkv)
+        qkv64 = qkv.astype(np.float64)
+        out = torch.full((M, d), float("nan"), dtype=torch.float32, device="cuda")
+    ref = np.concatenate([O.multi_head_attention(qkv64[a:b, :d], qkv64[a:b, d:2 * d], qkv64[a:b, 2 * d:], n_heads)
+                          for a, b in zip(cu[:-1], cu[1:])])
+    wf.op_attention(precision, t.cuda(), out, cu, n_heads)
+    got = out.float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    # bf16: P is rounded to bf16 before the P.V product and the output is bf16
+    assert _rel(got, ref) < (1e-2 if precision == wf.WF_PRECISION_BF16 else 1e-5)
