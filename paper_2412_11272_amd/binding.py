@@ -65,6 +65,9 @@ def lib() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2412_11272_amd.build`")
+    # PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  Import it first so that this
+    # library binds to that same runtime: device pointers and streams are only meaningful within one.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     L.wf_last_error.restype = C.c_char_p
     L.wf_encoder_create.argtypes = [C.POINTER(WfConfig), C.POINTER(WfWeights), C.POINTER(C.c_void_p)]
@@ -149,15 +152,15 @@ class Encoder:
         import torch
         B = len(n_frames)
         cu, _, M = plan_batch(self.cfg, n_frames) if 1 <= B <= self.cfg.max_streams else (np.zeros(B + 1, np.int32), 0, 0)
-        if out is None:
-            out = torch.empty((M, self.cfg.d_model), device=mel.device, dtype=out_dtype or torch.float32)
+        if out is None:      # at least one row, so that an invalid batch reaches the library's own checks
+            out = torch.empty((max(M, 1), self.cfg.d_model), device=mel.device, dtype=out_dtype or torch.float32)[:M]
         s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
         off = np.ascontiguousarray(frame_offset, dtype=np.int32)
         nf = np.ascontiguousarray(n_frames, dtype=np.int32)
         cu_out = np.zeros(B + 1, dtype=np.int32)
         _check(lib().wf_encode_batch(self._h, C.c_void_p(mel.data_ptr()), _torch_dtype_code(mel.dtype),
                                      off.ctypes.data_as(_ip), nf.ctypes.data_as(_ip), B,
-                                     C.c_void_p(out.data_ptr()), _torch_dtype_code(out.dtype), out.shape[0],
+                                     C.c_void_p(out.data_ptr() or out.untyped_storage().data_ptr()), _torch_dtype_code(out.dtype), out.shape[0],
                                      cu_out.ctypes.data_as(_ip), C.c_void_p(s)))
         return out, cu_out
 
