@@ -13,11 +13,45 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace wf {
 
 namespace {
 
 constexpr int BK = 64;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Global -> registers for one 64-wide K step of the tile (fully unrolled, values stay in VGPRs).
+template <int XCH, int WCH, int NT, int AMODE>
+__device__ __forceinline__ void load_tile(u32x4 (&xr)[XCH], u32x4 (&wr)[WCH], const __bf16 *const (&xptr)[XCH],
+                                          const int (&xflags)[XCH], const __bf16 *const (&wptr)[WCH], int k0, int C, int tid) {
+#pragma unroll
+  for (int i = 0; i < XCH; ++i) {
+    if (AMODE == A_PLAIN) {
+      xr[i] = *(const u32x4 *)(xptr[i] + k0);
+    } else {
+      const int kk = k0 + ((i * NT + tid) & 7) * 8;   // chunks never straddle taps: C % 8 == 0
+      const int tap = kk / C;
+      const bool ok = (kk < 3 * C) && !((tap == 0) && (xflags[i] & 1)) && !((tap == 2) && (xflags[i] & 2));
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (ok) v = *(const u32x4 *)(xptr[i] + k0);
+      xr[i] = v;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < WCH; ++i) wr[i] = *(const u32x4 *)(wptr[i] + k0);
+}
+
+template <int XCH, int WCH>
+__device__ __forceinline__ void store_tile(const u32x4 (&xr)[XCH], const u32x4 (&wr)[WCH], unsigned char *dx, unsigned char *dw,
+                                           const int (&xlds)[XCH], const int (&wlds)[WCH]) {
+#pragma unroll
+  for (int i = 0; i < XCH; ++i) *(u32x4 *)(dx + xlds[i]) = xr[i];
+#pragma unroll
+  for (int i = 0; i < WCH; ++i) *(u32x4 *)(dw + wlds[i]) = wr[i];
+}
 
 template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
@@ -80,32 +114,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
     wlds[i] = r * 128 + ((ch ^ (r & 7)) << 4);
   }
 
-  uint4 xr[XCH], wr[WCH];
-  auto load_tile = [&](int kt) {
-    const int k0 = kt * BK;
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) {
-      if (AMODE == A_PLAIN) {
-        xr[i] = *(const uint4 *)(xptr[i] + k0);
-      } else {
-        const int kk = k0 + ((i * NT + tid) & 7) * 8;   // chunks never straddle taps: C % 8 == 0
-        const int tap = kk / p.C;
-        const bool ok = (kk < 3 * p.C) && !((tap == 0) && (xflags[i] & 1)) && !((tap == 2) && (xflags[i] & 2));
-        xr[i] = ok ? *(const uint4 *)(xptr[i] + k0) : make_uint4(0, 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) wr[i] = *(const uint4 *)(wptr[i] + k0);
-  };
-  auto store_tile = [&](int stage) {
-    unsigned char *dx = sX + stage * BM * 128;
-    unsigned char *dw = sW + stage * BN * 128;
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) *(uint4 *)(dx + xlds[i]) = xr[i];
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) *(uint4 *)(dw + wlds[i]) = wr[i];
-  };
-
+  u32x4 xr[XCH], wr[WCH];
   f32x16 acc[IM][IN];
 #pragma unroll
   for (int i = 0; i < IM; ++i)
@@ -115,8 +124,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int nk = p.K / BK;
-  load_tile(0);
-  store_tile(0);
+  load_tile<XCH, WCH, NT, AMODE>(xr, wr, xptr, xflags, wptr, 0, p.C, tid);
+  store_tile<XCH, WCH>(xr, wr, sX, sW, xlds, wlds);
   __syncthreads();
 
   // fragment read offsets: lane reads row (l32) of a 32-row group, chunk 2*ks + lg (swizzled)
@@ -126,7 +135,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
 
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < nk) load_tile(kt + 1);
+    if (kt + 1 < nk) load_tile<XCH, WCH, NT, AMODE>(xr, wr, xptr, xflags, wptr, (kt + 1) * BK, p.C, tid);
     const unsigned char *cx = sX + stage * BM * 128 + xrow0;
     const unsigned char *cw = sW + stage * BN * 128 + wrow0;
 #pragma unroll
@@ -143,7 +152,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
         for (int j = 0; j < IN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tile(stage ^ 1);
+    if (kt + 1 < nk) store_tile<XCH, WCH>(xr, wr, sX + (stage ^ 1) * BM * 128, sW + (stage ^ 1) * BN * 128, xlds, wlds);
     __syncthreads();
   }
 
@@ -202,12 +211,26 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Tuning knob: WF_GEMM_TILE=<n> in the environment forces tile configuration n (see the switch).
+int forced_tile() {
+  static int v = [] { const char *e = getenv("WF_GEMM_TILE"); return e ? atoi(e) : -1; }();
+  return v;
+}
+
 template <int AMODE, int EPI>
 hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
   // Large tile when it divides N and there is enough work to fill 256 CUs with it.
   const bool big = (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
-  if (big) return launch_cfg<256, 256, 2, 4, AMODE, EPI>(a, s);
-  return launch_cfg<128, 128, 2, 2, AMODE, EPI>(a, s);
+  int cfg = big ? 0 : 3;
+  if (forced_tile() >= 0 && a.N % 256 == 0) cfg = forced_tile();
+  switch (cfg) {
+    case 0: return launch_cfg<256, 256, 2, 4, AMODE, EPI>(a, s);
+    case 1: return launch_cfg<256, 256, 2, 2, AMODE, EPI>(a, s);
+    case 2: return launch_cfg<256, 256, 4, 2, AMODE, EPI>(a, s);
+    case 4: return launch_cfg<256, 128, 2, 2, AMODE, EPI>(a, s);
+    case 5: return launch_cfg<128, 256, 2, 2, AMODE, EPI>(a, s);
+    default: return launch_cfg<128, 128, 2, 2, AMODE, EPI>(a, s);
+  }
 }
 
 }  // namespace
