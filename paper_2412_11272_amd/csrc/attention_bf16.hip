@@ -78,8 +78,8 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
     __syncthreads();                            // previous tile fully consumed
     {
       const int r0 = 2 * kp, r1 = r0 + 1;
-      *(uint4 *)(sK + r0 * 128 + ((ch ^ (r0 & 7)) << 4)) = k_a;
-      *(uint4 *)(sK + r1 * 128 + ((ch ^ (r1 & 7)) << 4)) = k_b;
+      *(uint4 *)(sK + r0 * 128 + ((ch ^ ((r0 >> 1) & 7)) << 4)) = k_a;
+      *(uint4 *)(sK + r1 * 128 + ((ch ^ ((r1 >> 1) & 7)) << 4)) = k_b;
       // transposed V: feature f = 8*ch + e, keys (2kp, 2kp+1) packed into one 32-bit word.
       // Row f is 16 units of 8 bytes (4 keys each); unit index is XOR-ed with (f & 15).
       const uint32_t va[4] = {v_a.x, v_a.y, v_a.z, v_a.w};
@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
       const int row = kb2 * 32 + l32;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 kf = *(const bf16x8 *)(sK + row * 128 + (((2 * ks + lg) ^ (row & 7)) << 4));
+        const bf16x8 kf = *(const bf16x8 *)(sK + row * 128 + (((2 * ks + lg) ^ ((row >> 1) & 7)) << 4));
         s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb2], 0, 0, 0);
       }
     }

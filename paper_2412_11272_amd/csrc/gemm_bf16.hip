@@ -8,8 +8,11 @@
 // (BM/WM) x (BN/WN) sub-tile built from v_mfma_f32_32x32x16_bf16.  The weight fragment is the MFMA's
 // first operand and the activation fragment the second, so a lane ends up holding four consecutive
 // output features of one token and the epilogue can store 8 or 16 contiguous bytes per lane.
-// LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row & 7) so that both
-// the row-per-lane fragment reads and the tile writes spread over all banks.
+// LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row >> 1) & 7.  The LDS
+// has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a time, so the 16 rows a
+// group of lanes touches must land on 16 distinct 16-byte bank groups: rows of equal parity share
+// the 128-byte half, and (row >> 1) & 7 gives them 8 distinct chunk positions (measured: 209 B/clk
+// per CU with this swizzle, 128 with XOR by row & 7, 32 with none).
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -102,7 +105,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
       xptr[i] = A + (long)p.row_src[row] * p.C + ch * 8;
       xflags[i] = p.row_flags[row];
     }
-    xlds[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+    xlds[i] = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   }
   const __bf16 *wptr[WCH];
   int wlds[WCH];
@@ -111,7 +114,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
     const int c = i * NT + tid;
     const int r = c >> 3, ch = c & 7;
     wptr[i] = W + (size_t)(n0 + r) * p.K + ch * 8;
-    wlds[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+    wlds[i] = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   }
 
   u32x4 xr[XCH], wr[WCH];
@@ -131,7 +134,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
   // fragment read offsets: lane reads row (l32) of a 32-row group, chunk 2*ks + lg (swizzled)
   const int xrow0 = (wm * TM + l32) * 128;
   const int wrow0 = (wn * TN + l32) * 128;
-  const int sw = l32 & 7;
+  const int sw = (l32 >> 1) & 7;
 
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = kt & 1;
@@ -211,6 +214,183 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Variant with direct global -> LDS loads (no VGPR staging) and register double-buffering of the
+// MFMA fragments.  global_load_lds_dwordx4 writes lane l's 16 bytes at LDS base + 16*l, so a wave
+// fills 8 consecutive 128-byte rows per instruction; the XOR swizzle is applied by choosing which
+// global chunk each lane fetches (lane l of a row group fetches chunk (l & 7) ^ (l >> 3)).
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) void glb_void;
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int IM = TM / 32, IN = TN / 32;
+  constexpr int XL = BM / 8 / NW;    // load instructions per wave for the activation tile (8 rows each)
+  constexpr int WL = BN / 8 / NW;
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char *sX = smem;                        // [2][BM][128 B]
+  unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
+
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int tiles_n = p.N / BN;
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= n_tiles) return;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, lg = lane >> 5;
+
+  // lane -> row within the 8-row group written by one load instruction; the chunk it fetches is the
+  // one that belongs at its LDS slot: (lane & 7) ^ swizzle(row)
+  const int lrow = lane >> 3;
+  const __bf16 *A = (const __bf16 *)p.A;
+  const __bf16 *W = (const __bf16 *)p.W;
+  const __bf16 *xptr[XL];
+  const __bf16 *wptr[WL];
+#pragma unroll
+  for (int i = 0; i < XL; ++i) {
+    const int rt = (i * NW + wave) * 8 + lrow;
+    const int lch = (lane & 7) ^ ((rt >> 1) & 7);
+    int row = m0 + rt;
+    row = row < p.M ? row : p.M - 1;              // rows past M are computed but never stored
+    xptr[i] = A + (size_t)row * p.lda + lch * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < WL; ++i) {
+    const int rt = (i * NW + wave) * 8 + lrow;
+    const int lch = (lane & 7) ^ ((rt >> 1) & 7);
+    wptr[i] = W + (size_t)(n0 + rt) * p.K + lch * 8;
+  }
+
+  auto issue = [&](int kt) {
+    const int stage = kt & 1;
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int i = 0; i < XL; ++i)
+      __builtin_amdgcn_global_load_lds((const glb_void *)(xptr[i] + k0),
+                                       (lds_void *)(sX + stage * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < WL; ++i)
+      __builtin_amdgcn_global_load_lds((const glb_void *)(wptr[i] + k0),
+                                       (lds_void *)(sW + stage * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[IM][IN];
+#pragma unroll
+  for (int i = 0; i < IM; ++i)
+#pragma unroll
+    for (int j = 0; j < IN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int nk = p.K / BK;
+  const int xrow0 = (wm * TM + l32) * 128;
+  const int wrow0 = (wn * TN + l32) * 128;
+  const int sw = (l32 >> 1) & 7;
+
+  // The two waves that share a SIMD issue their global loads at different points of the K step
+  // (the first at its start, the second after LATE k-steps), so that while one wave is held up
+  // handing its loads to the memory pipeline the other keeps the matrix pipe busy.
+  const bool early = (wave < NW / 2) || NW < 8;
+  constexpr int LATE = 1;
+  issue(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's part of tile kt is in LDS
+    __builtin_amdgcn_s_barrier();                  // ... and everyone's; stage^1 is no longer being read
+    if (kt + 1 < nk && early) issue(kt + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char *cx = sX + stage * BM * 128 + xrow0;
+    const unsigned char *cw = sW + stage * BN * 128 + wrow0;
+    bf16x8 wf[2][IN], xf[2][IM];
+    {
+      const int choff = ((0 + lg) ^ sw) << 4;
+#pragma unroll
+      for (int j = 0; j < IN; ++j) wf[0][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
+#pragma unroll
+      for (int i = 0; i < IM; ++i) xf[0][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks < 3) {                                // fragments of the next k-step, in flight during this step's MFMAs
+        const int choff = ((2 * (ks + 1) + lg) ^ sw) << 4;
+#pragma unroll
+        for (int j = 0; j < IN; ++j) wf[nxt][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
+#pragma unroll
+        for (int i = 0; i < IM; ++i) xf[nxt][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < IN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks == LATE - 1) {
+        if (kt + 1 < nk && !early) issue(kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < IM; ++i) {
+    const int m = m0 + wm * TM + i * 32 + l32;
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < IN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn * TN + j * 32 + g * 8 + lg * 4;
+        const f32x4 b = *(const f32x4 *)(p.bias + n);
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
+        if (EPI == EPI_BIAS) {
+          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
+        } else if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
+          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
+        } else {
+          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + n);
+          const f32x4 x = *o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += x[e];
+          *o = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
+  constexpr int smem = 2 * (BM + BN) * 128;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
+  const int grid = ((tiles + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  return hipGetLastError();
+}
+
 // Tuning knob: WF_GEMM_TILE=<n> in the environment forces tile configuration n (see the switch).
 int forced_tile() {
   static int v = [] { const char *e = getenv("WF_GEMM_TILE"); return e ? atoi(e) : -1; }();
@@ -221,8 +401,15 @@ template <int AMODE, int EPI>
 hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
   // Large tile when it divides N and there is enough work to fill 256 CUs with it.
   const bool big = (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
-  int cfg = big ? 0 : 3;
+  constexpr bool direct = (AMODE == A_PLAIN && EPI != EPI_BIAS_GELU_POS);   // gathered operands keep the register-staged kernel
+  int cfg = direct ? (big ? 10 : 13) : (big ? 2 : 3);
   if (forced_tile() >= 0 && a.N % 256 == 0) cfg = forced_tile();
+  if constexpr (direct) {
+    if (cfg == 10) return launch_dl<256, 256, 4, 2, EPI>(a, s);
+    if (cfg == 11) return launch_dl<256, 256, 2, 4, EPI>(a, s);
+    if (cfg == 12) return launch_dl<256, 256, 2, 2, EPI>(a, s);
+    if (cfg == 13) return launch_dl<128, 128, 2, 2, EPI>(a, s);
+  }
   switch (cfg) {
     case 0: return launch_cfg<256, 256, 2, 4, AMODE, EPI>(a, s);
     case 1: return launch_cfg<256, 256, 2, 2, AMODE, EPI>(a, s);
