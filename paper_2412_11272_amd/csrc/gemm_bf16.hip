@@ -344,33 +344,88 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
     }
   }
 
+  // ---- epilogue.  The accumulator layout gives a lane 4 consecutive features of ONE token, which would
+  // make every store instruction touch 32 different rows.  Each wave therefore transposes its sub-tile
+  // through its own 16 KB slice of the (now idle) LDS stages and writes whole 128/256-byte row
+  // segments: 16-byte chunk c of row r sits at chunk position c ^ (r & (CPR-1)).
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __builtin_amdgcn_s_barrier();                    // every wave is done reading the last K step
+  unsigned char *stg = smem + wave * (TM * 256);   // TM rows x 256 bytes (<= 16 KB per wave)
+  static_assert(NW * TM * 256 <= 2 * (BM + BN) * 128, "staging does not fit in the LDS stages");
+  const int mw0 = m0 + wm * TM, nw0 = n0 + wn * TN;
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
+    constexpr int RB = TN * 2;                     // row bytes (bf16)
+    constexpr int CPR = RB / 16;                   // 16-byte chunks per row
 #pragma unroll
-  for (int i = 0; i < IM; ++i) {
-    const int m = m0 + wm * TM + i * 32 + l32;
-    if (m >= p.M) continue;
+    for (int i = 0; i < IM; ++i) {
+      const int r = i * 32 + l32;
 #pragma unroll
-    for (int j = 0; j < IN; ++j) {
+      for (int j = 0; j < IN; ++j) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * TN + j * 32 + g * 8 + lg * 4;
-        const f32x4 b = *(const f32x4 *)(p.bias + n);
-        f32x4 v;
+        for (int g = 0; g < 4; ++g) {
+          const int nl = j * 32 + g * 8 + lg * 4;  // feature inside the wave's sub-tile
+          const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
+          f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
-        if (EPI == EPI_BIAS) {
-          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
-        } else if (EPI == EPI_BIAS_GELU) {
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
+          if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
-          *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + n) = to_bf16x4(v);
-        } else {
-          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + n);
-          const f32x4 x = *o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += x[e];
-          *o = v;
+            for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
+          }
+          const int u = nl >> 2;                   // 8-byte unit inside the row
+          *(bf16x4 *)(stg + r * RB + ((((u >> 1) ^ (r & (CPR - 1))) << 4) | ((u & 1) << 3))) = to_bf16x4(v);
         }
       }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): the wave's own LDS writes have landed
+    constexpr int RPI = 64 / CPR;                  // rows per store instruction
+    const int rr = lane / CPR, c = lane % CPR;
+#pragma unroll
+    for (int it = 0; it < TM / RPI; ++it) {
+      const int r = it * RPI + rr;
+      const u32x4 v = *(const u32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
+      const int m = mw0 + r;
+      if (m < p.M) *(u32x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nw0 + c * 8) = v;
+    }
+  } else {
+    // fp32 residual update in place, 64 features (256 bytes per row) per pass
+    constexpr int CPR = 16;
+#pragma unroll
+    for (int ps = 0; ps < TN / 64; ++ps) {
+#pragma unroll
+      for (int i = 0; i < IM; ++i) {
+        const int r = i * 32 + l32;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const int j = ps * 2 + jj;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int nl = j * 32 + g * 8 + lg * 4;
+            const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
+            const int ch = (nl & 63) >> 2;         // 16-byte chunk inside the 64-feature pass
+            *(f32x4 *)(stg + r * 256 + ((ch ^ (r & (CPR - 1))) << 4)) = v;
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      const int rr = lane >> 4, c = lane & 15;
+#pragma unroll
+      for (int it = 0; it < TM / 4; ++it) {
+        const int r = it * 4 + rr;
+        const f32x4 v = *(const f32x4 *)(stg + r * 256 + ((c ^ (r & (CPR - 1))) << 4));
+        const int m = mw0 + r;
+        if (m < p.M) {
+          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * 64 + c * 4);
+          f32x4 x = *o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] += v[e];
+          *o = x;
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);          // reads done before the next pass overwrites the slice
     }
   }
 }
@@ -406,8 +461,6 @@ hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
   if (forced_tile() >= 0 && a.N % 256 == 0) cfg = forced_tile();
   if constexpr (direct) {
     if (cfg == 10) return launch_dl<256, 256, 4, 2, EPI>(a, s);
-    if (cfg == 11) return launch_dl<256, 256, 2, 4, EPI>(a, s);
-    if (cfg == 12) return launch_dl<256, 256, 2, 2, EPI>(a, s);
     if (cfg == 13) return launch_dl<128, 128, 2, 2, EPI>(a, s);
   }
   switch (cfg) {
