@@ -22,9 +22,29 @@ namespace {
 constexpr int BQ = 128;    // queries per work item
 constexpr int BKV = 64;    // keys per tile
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Tile staging: K row-major [key][64 features] with the 16-byte chunk XOR-ed by (key >> 1) & 7, and
+// V transposed [feature][64 keys] in 8-byte units (4 keys) XOR-ed by feature & 15.
+__device__ __forceinline__ void stage_kv(unsigned char *sK, unsigned char *sVt, const u32x4 &k_a, const u32x4 &k_b,
+                                         const u32x4 &v_a, const u32x4 &v_b, int kp, int ch) {
+  const int r0 = 2 * kp, r1 = r0 + 1;
+  *(u32x4 *)(sK + r0 * 128 + ((ch ^ ((r0 >> 1) & 7)) << 4)) = k_a;
+  *(u32x4 *)(sK + r1 * 128 + ((ch ^ ((r1 >> 1) & 7)) << 4)) = k_b;
+  // feature f = 8*ch + e; keys (2kp, 2kp+1) of that feature packed into one 32-bit word
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t a = v_a[e >> 1], b = v_b[e >> 1];
+    const uint32_t w = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+    const int f = 8 * ch + e;
+    const int unit = (kp >> 1) ^ (f & 15);
+    *(uint32_t *)(sVt + f * 128 + unit * 8 + (kp & 1) * 4) = w;
+  }
+}
+
 __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
-  __shared__ __attribute__((aligned(16))) unsigned char sK[BKV * 128];    // [key][64 feat] swizzled
-  __shared__ __attribute__((aligned(16))) unsigned char sVt[64 * 128];    // [feat][64 keys] swizzled
+  __shared__ __attribute__((aligned(16))) unsigned char sK[2][BKV * 128];
+  __shared__ __attribute__((aligned(16))) unsigned char sVt[2][64 * 128];
 
   const int item = blockIdx.x / p.n_heads;
   const int head = blockIdx.x % p.n_heads;
@@ -64,110 +84,104 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
 
   // cooperative load mapping: thread -> (key pair kp, 16-byte feature chunk ch)
   const int kp = tid >> 3, ch = tid & 7;
-
-  const int n_tiles = (L + BKV - 1) / BKV;
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    const int key0 = kt * BKV;
-    int ka = key0 + 2 * kp, kb = ka + 1;
+  u32x4 k_a, k_b, v_a, v_b;
+  auto fetch = [&](int kt) {
+    int ka = kt * BKV + 2 * kp, kb = ka + 1;
     ka = ka < L ? ka : L - 1;                   // clamped rows are masked out of the softmax below
     kb = kb < L ? kb : L - 1;
-    const uint4 k_a = *(const uint4 *)(Kb + (size_t)ka * ld + ch * 8);
-    const uint4 k_b = *(const uint4 *)(Kb + (size_t)kb * ld + ch * 8);
-    const uint4 v_a = *(const uint4 *)(Vb + (size_t)ka * ld + ch * 8);
-    const uint4 v_b = *(const uint4 *)(Vb + (size_t)kb * ld + ch * 8);
-    __syncthreads();                            // previous tile fully consumed
-    {
-      const int r0 = 2 * kp, r1 = r0 + 1;
-      *(uint4 *)(sK + r0 * 128 + ((ch ^ ((r0 >> 1) & 7)) << 4)) = k_a;
-      *(uint4 *)(sK + r1 * 128 + ((ch ^ ((r1 >> 1) & 7)) << 4)) = k_b;
-      // transposed V: feature f = 8*ch + e, keys (2kp, 2kp+1) packed into one 32-bit word.
-      // Row f is 16 units of 8 bytes (4 keys each); unit index is XOR-ed with (f & 15).
-      const uint32_t va[4] = {v_a.x, v_a.y, v_a.z, v_a.w};
-      const uint32_t vb[4] = {v_b.x, v_b.y, v_b.z, v_b.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t lo = (e & 1) ? (va[e >> 1] >> 16) : (va[e >> 1] & 0xffffu);
-        const uint32_t hi = (e & 1) ? (vb[e >> 1] >> 16) : (vb[e >> 1] & 0xffffu);
-        const int f = 8 * ch + e;
-        const int unit = (kp >> 1) ^ (f & 15);
-        *(uint32_t *)(sVt + f * 128 + unit * 8 + (kp & 1) * 4) = lo | (hi << 16);
-      }
-    }
-    __syncthreads();
-    if (!wave_active) continue;
+    k_a = *(const u32x4 *)(Kb + (size_t)ka * ld + ch * 8);
+    k_b = *(const u32x4 *)(Kb + (size_t)kb * ld + ch * 8);
+    v_a = *(const u32x4 *)(Vb + (size_t)ka * ld + ch * 8);
+    v_b = *(const u32x4 *)(Vb + (size_t)kb * ld + ch * 8);
+  };
 
-    // ---- S^T = K Q^T : two 32-key blocks, reduction over the 64 features in 4 steps
-    f32x16 s[2];
+  const int n_tiles = (L + BKV - 1) / BKV;
+  fetch(0);
+  stage_kv(sK[0], sVt[0], k_a, k_b, v_a, v_b, kp, ch);
+  __syncthreads();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int key0 = kt * BKV;
+    const unsigned char *cK = sK[kt & 1], *cVt = sVt[kt & 1];
+    if (kt + 1 < n_tiles) fetch(kt + 1);        // in flight while this tile is being used
+    if (wave_active) {
+      // ---- S^T = K Q^T : two 32-key blocks, reduction over the 64 features in 4 steps
+      f32x16 s[2];
 #pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2) {
+      for (int kb2 = 0; kb2 < 2; ++kb2) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb2][r] = 0.0f;
-      const int row = kb2 * 32 + l32;
+        for (int r = 0; r < 16; ++r) s[kb2][r] = 0.0f;
+        const int row = kb2 * 32 + l32;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 kf = *(const bf16x8 *)(sK + row * 128 + (((2 * ks + lg) ^ ((row >> 1) & 7)) << 4));
-        s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb2], 0, 0, 0);
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 kf = *(const bf16x8 *)(cK + row * 128 + (((2 * ks + lg) ^ ((row >> 1) & 7)) << 4));
+          s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb2], 0, 0, 0);
+        }
       }
-    }
-    // lane holds logits of query l32 against keys key0 + 32*kb2 + 8*(r/4) + 4*lg + r%4
-    if (key0 + BKV > L) {
+      // lane holds logits of query l32 against keys key0 + 32*kb2 + 8*(r/4) + 4*lg + r%4
+      if (key0 + BKV > L) {
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = key0 + kb2 * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+            if (key >= L) s[kb2][r] = -INFINITY;
+          }
+      }
+      float tmax = s[0][0];
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kb2 * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-          if (key >= L) s[kb2][r] = -INFINITY;
-        }
-    }
-    float tmax = s[0][0];
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb2][r]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m_run, tmax);       // finite: every tile has at least one valid key
+      if (__any(m_new > m_run)) {                   // rescale only when some query's maximum moved
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        l_run *= alpha;
 #pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb2][r]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m_run, tmax);       // finite: every tile has at least one valid key
-    const float alpha = exp2f((m_run - m_new) * c);
-    m_run = m_new;
-    const float mc = m_new * c;
-    float psum = 0.0f;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        f32x4 e0, e1;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          e0[e] = exp2f(s[kb2][8 * h + e] * c - mc);
-          e1[e] = exp2f(s[kb2][8 * h + 4 + e] * c - mc);
-          psum += e0[e] + e1[e];
-        }
-        const bf16x4 b0 = to_bf16x4(e0), b1 = to_bf16x4(e1);
-        pf[kb2][h] = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+          for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+        m_run = m_new;
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
-
-    // ---- O^T += V^T P^T.  Reduction step (kb2, h) covers the 16 keys the lane pair holds in
-    // pf[kb2][h]: group lg has keys 32*kb2 + 16*h + 4*lg + (0..3) and the same + 8.
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int f = t * 32 + l32;
-      const unsigned char *vrow = sVt + f * 128;
+      const float mc = m_run * c;
+      float psum = 0.0f;
+      bf16x8 pf[2][2];
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          const int u0 = (kb2 * 32 + 16 * h + 4 * lg) >> 2;      // 8-byte unit of the first 4 keys
-          const bf16x4 v0 = *(const bf16x4 *)(vrow + ((u0 ^ (f & 15)) << 3));
-          const bf16x4 v1 = *(const bf16x4 *)(vrow + (((u0 + 2) ^ (f & 15)) << 3));
-          const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb2][h], o[t], 0, 0, 0);
+          f32x4 e0, e1;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            e0[e] = __builtin_amdgcn_exp2f(s[kb2][8 * h + e] * c - mc);
+            e1[e] = __builtin_amdgcn_exp2f(s[kb2][8 * h + 4 + e] * c - mc);
+            psum += e0[e] + e1[e];
+          }
+          const bf16x4 b0 = to_bf16x4(e0), b1 = to_bf16x4(e1);
+          pf[kb2][h] = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
         }
+      l_run += psum;
+
+      // ---- O^T += V^T P^T.  Reduction step (kb2, h) covers the 16 keys the lane pair holds in
+      // pf[kb2][h]: group lg has keys 32*kb2 + 16*h + 4*lg + (0..3) and the same + 8.
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int f = t * 32 + l32;
+        const unsigned char *vrow = cVt + f * 128;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int u0 = (kb2 * 32 + 16 * h + 4 * lg) >> 2;      // 8-byte unit of the first 4 keys
+            const bf16x4 v0 = *(const bf16x4 *)(vrow + ((u0 ^ (f & 15)) << 3));
+            const bf16x4 v1 = *(const bf16x4 *)(vrow + (((u0 + 2) ^ (f & 15)) << 3));
+            const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb2][h], o[t], 0, 0, 0);
+          }
+      }
     }
+    if (kt + 1 < n_tiles) stage_kv(sK[(kt + 1) & 1], sVt[(kt + 1) & 1], k_a, k_b, v_a, v_b, kp, ch);
+    __syncthreads();                            // next tile staged, this one no longer read
   }
 
   if (!wave_active) return;
