@@ -298,51 +298,65 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   const int wrow0 = (wn * TN + l32) * 128;
   const int sw = (l32 >> 1) & 7;
 
-  // The two waves that share a SIMD issue their global loads at different points of the K step
-  // (the first at its start, the second after LATE k-steps), so that while one wave is held up
-  // handing its loads to the memory pipeline the other keeps the matrix pipe busy.
+  // Main loop.  Fragments are double-buffered in registers: the reads of k-step s+1 are issued, then the
+  // 8 MFMAs of k-step s run while they are in flight.  The one barrier per K step of 64 sits right after
+  // the LAST fragment read of the current tile: at that point (a) every wave has finished reading this
+  // LDS stage, so the loads of tile kt+2 may overwrite it, and (b) every wave has seen its own loads of
+  // tile kt+1 land, so its first fragments can be read under the MFMAs of k-step 3 -- the matrix pipe
+  // never drains at the barrier.  The two waves that share a SIMD issue their global loads at
+  // different points (before / after those MFMAs), so one keeps the matrix pipe busy while the other
+  // is held up handing loads to the memory pipeline.
   const bool early = (wave < NW / 2) || NW < 8;
-  constexpr int LATE = 1;
-  issue(0);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's part of tile kt is in LDS
-    __builtin_amdgcn_s_barrier();                  // ... and everyone's; stage^1 is no longer being read
-    if (kt + 1 < nk && early) issue(kt + 1);
-    __builtin_amdgcn_sched_barrier(0);
+  bf16x8 wf[2][IN], xf[2][IM];
+  auto rd = [&](int stage, int ks, int buf) {
     const unsigned char *cx = sX + stage * BM * 128 + xrow0;
     const unsigned char *cw = sW + stage * BN * 128 + wrow0;
-    bf16x8 wf[2][IN], xf[2][IM];
-    {
-      const int choff = ((0 + lg) ^ sw) << 4;
+    const int choff = ((2 * ks + lg) ^ sw) << 4;
 #pragma unroll
-      for (int j = 0; j < IN; ++j) wf[0][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
+    for (int j = 0; j < IN; ++j) wf[buf][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
 #pragma unroll
-      for (int i = 0; i < IM; ++i) xf[0][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
-    }
+    for (int i = 0; i < IM; ++i) xf[buf][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
+  };
+  auto mm = [&](int buf) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks < 3) {                                // fragments of the next k-step, in flight during this step's MFMAs
-        const int choff = ((2 * (ks + 1) + lg) ^ sw) << 4;
+    for (int i = 0; i < IM; ++i)
 #pragma unroll
-        for (int j = 0; j < IN; ++j) wf[nxt][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
-#pragma unroll
-        for (int i = 0; i < IM; ++i) xf[nxt][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < IM; ++i)
-#pragma unroll
-        for (int j = 0; j < IN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (ks == LATE - 1) {
-        if (kt + 1 < nk && !early) issue(kt + 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+      for (int j = 0; j < IN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
+  };
+  // lgkmcnt(0) placed BEFORE the next reads are issued, so that it only waits for the older ones
+#define WF_STEP(stage, ks_next, buf_next, buf_cur)  \
+  __builtin_amdgcn_s_waitcnt(0xC07F);               \
+  __builtin_amdgcn_sched_barrier(0);                \
+  rd(stage, ks_next, buf_next);                     \
+  __builtin_amdgcn_sched_barrier(0);                \
+  mm(buf_cur);                                      \
+  __builtin_amdgcn_sched_barrier(0)
+
+  issue(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  if (1 < nk) issue(1);
+  rd(0, 0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st = kt & 1;
+    __builtin_amdgcn_sched_barrier(0);
+    WF_STEP(st, 1, 1, 0);
+    WF_STEP(st, 2, 0, 1);
+    WF_STEP(st, 3, 1, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): stage st fully read, my part of tile kt+1 landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 2 < nk && early) issue(kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 1 < nk) rd(st ^ 1, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 2 < nk && !early) issue(kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
   }
+#undef WF_STEP
 
   // ---- epilogue.  The accumulator layout gives a lane 4 consecutive features of ONE token, which would
   // make every store instruction touch 32 different rows.  Each wave therefore transposes its sub-tile
