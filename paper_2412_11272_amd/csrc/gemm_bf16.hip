@@ -71,14 +71,22 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
 
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own L2), so
   // give every XCD a contiguous run of tiles: tiles that share activation rows then share an L2.
+  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
+  // every XCD gets a contiguous run of the tile order, and the order walks the output in column groups
+  // of p.group_n tile columns: inside a group, tile row by tile row.  The tiles an XCD runs at one time
+  // then share a few weight panels (which stay in its L2) and a few activation panels.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
   const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile >= n_tiles) return;
-  const int m0 = (tile / tiles_n) * BM;
-  const int n0 = (tile % tiles_n) * BN;
+  const int group_n = max(1, min(p.group_n, tiles_n));
+  const int per_group = tiles_m * group_n;
+  const int grp = tile / per_group, rem = tile - grp * per_group;
+  const int gn = min(group_n, tiles_n - grp * group_n);
+  const int m0 = (rem / gn) * BM;
+  const int n0 = (grp * group_n + rem % gn) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -198,6 +206,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
   }
 }
 
+// Tuning knob: WF_GEMM_GROUP_N=<n> forces the number of tile columns per column group.
+int forced_group() {
+  static int v = [] { const char *e = getenv("WF_GEMM_GROUP_N"); return e ? atoi(e) : -1; }();
+  return v;
+}
+
+// Column group of the tile order: as many weight panels as fit in about 2.5 MB of an XCD's L2.
+int column_group(int bn, int n, int k) {
+  int gn = (int)(2621440L / ((long)bn * k * 2));
+  if (forced_group() > 0) gn = forced_group();
+  const int tiles_n = n / bn;
+  return gn < 1 ? 1 : (gn > tiles_n ? tiles_n : gn);
+}
+
 template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
 hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
@@ -210,7 +232,9 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const int grid = ((tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  GemmArgs b = a;
+  b.group_n = column_group(BN, a.N, a.K);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
   return hipGetLastError();
 }
 
@@ -235,14 +259,22 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   unsigned char *sX = smem;                        // [2][BM][128 B]
   unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
 
+  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
+  // every XCD gets a contiguous run of the tile order, and the order walks the output in column groups
+  // of p.group_n tile columns: inside a group, tile row by tile row.  The tiles an XCD runs at one time
+  // then share a few weight panels (which stay in its L2) and a few activation panels.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
   const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile >= n_tiles) return;
-  const int m0 = (tile / tiles_n) * BM;
-  const int n0 = (tile % tiles_n) * BN;
+  const int group_n = max(1, min(p.group_n, tiles_n));
+  const int per_group = tiles_m * group_n;
+  const int grp = tile / per_group, rem = tile - grp * per_group;
+  const int gn = min(group_n, tiles_n - grp * group_n);
+  const int m0 = (rem / gn) * BM;
+  const int n0 = (grp * group_n + rem % gn) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -444,6 +476,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   }
 }
 
+
 template <int BM, int BN, int WM, int WN, int EPI>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
@@ -456,7 +489,9 @@ hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const int grid = ((tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  GemmArgs b = a;
+  b.group_n = column_group(BN, a.N, a.K);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
   return hipGetLastError();
 }
 
