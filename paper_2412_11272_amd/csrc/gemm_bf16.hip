@@ -72,9 +72,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own L2), so
   // give every XCD a contiguous run of tiles: tiles that share activation rows then share an L2.
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
-  // every XCD gets a contiguous run of the tile order, and the order walks the output in column groups
-  // of p.group_n tile columns: inside a group, tile row by tile row.  The tiles an XCD runs at one time
-  // then share a few weight panels (which stay in its L2) and a few activation panels.
+  // every XCD gets a contiguous run of the tile order; the order walks the output in column groups of
+  // p.group_n tile columns (default: all of them), tile row by tile row inside a group.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
@@ -212,11 +211,15 @@ int forced_group() {
   return v;
 }
 
-// Column group of the tile order: as many weight panels as fit in about 2.5 MB of an XCD's L2.
+// Column group of the tile order.  Default: all tile columns in one group, i.e. tile row by tile row, so
+// every XCD owns a distinct range of activation rows (each activation panel enters exactly one L2, once)
+// and re-reads the much smaller weight matrix, which stays in the memory-side cache.  Narrower groups
+// (weight panels pinned in L2, activations re-streamed once per group) measured 2 % slower end to end.
 int column_group(int bn, int n, int k) {
-  int gn = (int)(2621440L / ((long)bn * k * 2));
-  if (forced_group() > 0) gn = forced_group();
+  (void)k;
   const int tiles_n = n / bn;
+  int gn = tiles_n;
+  if (forced_group() > 0) gn = forced_group();
   return gn < 1 ? 1 : (gn > tiles_n ? tiles_n : gn);
 }
 
@@ -260,9 +263,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
 
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
-  // every XCD gets a contiguous run of the tile order, and the order walks the output in column groups
-  // of p.group_n tile columns: inside a group, tile row by tile row.  The tiles an XCD runs at one time
-  // then share a few weight panels (which stay in its L2) and a few activation panels.
+  // every XCD gets a contiguous run of the tile order; the order walks the output in column groups of
+  // p.group_n tile columns (default: all of them), tile row by tile row inside a group.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
