@@ -142,11 +142,12 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom["name"])
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom["name"], {}).get("total_bytes")
         except Exception:
             traffic = None
     roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_unit": "bytes per launch (L2 fill + write-back, rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, calibrated)",
+                "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
                 "avg_launch_ms": round(dom["total_ms"] / dom["launches"], 4),
                 "flops_per_launch": dom["flops"] / dom["launches"],
                 "ms_per_step_profiled": round(dt_prof * 1e3, 3)}
