@@ -1,22 +1,31 @@
-// bf16 MFMA GEMM for gfx950:  out = epilogue(A . W^T),  A [M, K] activations, W [N, K] weights,
-// fp32 accumulation.  Used for the QKV / out / fc1 / fc2 projections and, with a gathered A
-// operand, for both convolutions of the stem (a width-3 convolution over a packed time-major
-// matrix is a GEMM whose A row is the contiguous window of three frames).
+// bf16 MFMA GEMMs for gfx950:  out = epilogue(A . W^T),  A [M, K] activations, W [N, K] weights, fp32
+// accumulation, built from v_mfma_f32_32x32x16_bf16.  Two kernels share the tiling:
 //
-// Tiling: one workgroup computes a BM x BN tile; the K loop advances 64 elements at a time through
-// two LDS stages (global -> registers -> LDS, one barrier per step).  Each wave owns a
-// (BM/WM) x (BN/WN) sub-tile built from v_mfma_f32_32x32x16_bf16.  The weight fragment is the MFMA's
-// first operand and the activation fragment the second, so a lane ends up holding four consecutive
-// output features of one token and the epilogue can store 8 or 16 contiguous bytes per lane.
+//   gemm_bf16_dl_kernel   the projections of a transformer block (QKV, out, fc1, fc2).  Operand tiles go
+//                         global -> LDS directly (global_load_lds_dwordx4), fragments are double-buffered
+//                         in registers, the epilogue is transposed through LDS so that stores cover whole
+//                         row segments.
+//   gemm_bf16_kernel      the two convolutions of the stem: a width-3 convolution over a packed time-major
+//                         matrix is a GEMM whose A row is the contiguous window of three frames, with the
+//                         first / last tap zeroed at stream boundaries.  The masking needs the operand in
+//                         registers, so tiles go global -> registers -> LDS.
+//
+// Tiling: one workgroup computes a BM x BN tile and advances K by 64 through two LDS stages; each wave
+// owns a (BM/WM) x (BN/WN) sub-tile.  The weight fragment is the MFMA's first operand and the activation
+// fragment the second, so a lane ends up holding four consecutive output features of one token.
 // LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row >> 1) & 7.  The LDS
 // has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a time, so the 16 rows a
 // group of lanes touches must land on 16 distinct 16-byte bank groups: rows of equal parity share
 // the 128-byte half, and (row >> 1) & 7 gives them 8 distinct chunk positions (measured: 209 B/clk
 // per CU with this swizzle, 128 with XOR by row & 7, 32 with none).
+//
+// Workgroup -> tile: consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so every
+// XCD gets a contiguous run of the row-major tile order: it owns a range of activation rows (each
+// activation panel enters exactly one L2, once) and re-reads the much smaller weight matrix, which the
+// memory-side cache keeps.  (Walking the tiles in column groups of 4-5 weight panels halves the L2 fill
+// traffic but measured 2 % slower end to end.)
 #include "device_utils.h"
 #include "kernels.h"
-
-#include <cstdlib>
 
 namespace wf {
 
@@ -69,23 +78,14 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
   unsigned char *sX = smem;                        // [2][BM][128 B]
   unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
 
-  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own L2), so
-  // give every XCD a contiguous run of tiles: tiles that share activation rows then share an L2.
-  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
-  // every XCD gets a contiguous run of the tile order; the order walks the output in column groups of
-  // p.group_n tile columns (default: all of them), tile row by tile row inside a group.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);   // XCD x runs tiles [x*per_xcd, (x+1)*per_xcd)
   if (tile >= n_tiles) return;
-  const int group_n = max(1, min(p.group_n, tiles_n));
-  const int per_group = tiles_m * group_n;
-  const int grp = tile / per_group, rem = tile - grp * per_group;
-  const int gn = min(group_n, tiles_n - grp * group_n);
-  const int m0 = (rem / gn) * BM;
-  const int n0 = (grp * group_n + rem % gn) * BN;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -205,24 +205,6 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_kernel(GemmArgs p) {
   }
 }
 
-// Tuning knob: WF_GEMM_GROUP_N=<n> forces the number of tile columns per column group.
-int forced_group() {
-  static int v = [] { const char *e = getenv("WF_GEMM_GROUP_N"); return e ? atoi(e) : -1; }();
-  return v;
-}
-
-// Column group of the tile order.  Default: all tile columns in one group, i.e. tile row by tile row, so
-// every XCD owns a distinct range of activation rows (each activation panel enters exactly one L2, once)
-// and re-reads the much smaller weight matrix, which stays in the memory-side cache.  Narrower groups
-// (weight panels pinned in L2, activations re-streamed once per group) measured 2 % slower end to end.
-int column_group(int bn, int n, int k) {
-  (void)k;
-  const int tiles_n = n / bn;
-  int gn = tiles_n;
-  if (forced_group() > 0) gn = forced_group();
-  return gn < 1 ? 1 : (gn > tiles_n ? tiles_n : gn);
-}
-
 template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
 hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
@@ -235,9 +217,7 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const int grid = ((tiles + 7) / 8) * 8;
-  GemmArgs b = a;
-  b.group_n = column_group(BN, a.N, a.K);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
   return hipGetLastError();
 }
 
@@ -262,21 +242,14 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   unsigned char *sX = smem;                        // [2][BM][128 B]
   unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
 
-  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (each with its own 4 MB L2), so
-  // every XCD gets a contiguous run of the tile order; the order walks the output in column groups of
-  // p.group_n tile columns (default: all of them), tile row by tile row inside a group.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = p.N / BN;
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);   // XCD x runs tiles [x*per_xcd, (x+1)*per_xcd)
   if (tile >= n_tiles) return;
-  const int group_n = max(1, min(p.group_n, tiles_n));
-  const int per_group = tiles_m * group_n;
-  const int grp = tile / per_group, rem = tile - grp * per_group;
-  const int gn = min(group_n, tiles_n - grp * group_n);
-  const int m0 = (rem / gn) * BM;
-  const int n0 = (grp * group_n + rem % gn) * BN;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -491,37 +464,13 @@ hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const int grid = ((tiles + 7) / 8) * 8;
-  GemmArgs b = a;
-  b.group_n = column_group(BN, a.N, a.K);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
   return hipGetLastError();
 }
 
-// Tuning knob: WF_GEMM_TILE=<n> in the environment forces tile configuration n (see the switch).
-int forced_tile() {
-  static int v = [] { const char *e = getenv("WF_GEMM_TILE"); return e ? atoi(e) : -1; }();
-  return v;
-}
-
-template <int AMODE, int EPI>
-hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
-  // Large tile when it divides N and there is enough work to fill 256 CUs with it.
-  const bool big = (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
-  constexpr bool direct = (AMODE == A_PLAIN && EPI != EPI_BIAS_GELU_POS);   // gathered operands keep the register-staged kernel
-  int cfg = direct ? (big ? 10 : 13) : (big ? 2 : 3);
-  if (forced_tile() >= 0 && a.N % 256 == 0) cfg = forced_tile();
-  if constexpr (direct) {
-    if (cfg == 10) return launch_dl<256, 256, 4, 2, EPI>(a, s);
-    if (cfg == 13) return launch_dl<128, 128, 2, 2, EPI>(a, s);
-  }
-  switch (cfg) {
-    case 0: return launch_cfg<256, 256, 2, 4, AMODE, EPI>(a, s);
-    case 1: return launch_cfg<256, 256, 2, 2, AMODE, EPI>(a, s);
-    case 2: return launch_cfg<256, 256, 4, 2, AMODE, EPI>(a, s);
-    case 4: return launch_cfg<256, 128, 2, 2, AMODE, EPI>(a, s);
-    case 5: return launch_cfg<128, 256, 2, 2, AMODE, EPI>(a, s);
-    default: return launch_cfg<128, 128, 2, 2, AMODE, EPI>(a, s);
-  }
+// Large tile when it divides N and there is enough work to fill 256 CUs with it.
+bool use_large_tile(const GemmArgs &a) {
+  return (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
 }
 
 }  // namespace
@@ -529,19 +478,27 @@ hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
 hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   if (a.N % 128 != 0 || a.K % BK != 0 || a.K <= 0) return hipErrorInvalidValue;
+  const bool big = use_large_tile(a);
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
     switch (epi) {
-      case EPI_BIAS: return launch_shape<A_PLAIN, EPI_BIAS>(a, s);
-      case EPI_BIAS_GELU: return launch_shape<A_PLAIN, EPI_BIAS_GELU>(a, s);
-      case EPI_BIAS_RESID: return launch_shape<A_PLAIN, EPI_BIAS_RESID>(a, s);
+      case EPI_BIAS:
+        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS>(a, s);
+      case EPI_BIAS_GELU:
+        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU>(a, s);
+      case EPI_BIAS_RESID:
+        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_RESID>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_RESID>(a, s);
       default: return hipErrorInvalidValue;
     }
   }
-  if (a.C % 8 != 0 || 3 * a.C > a.K) return hipErrorInvalidValue;
+  if (a.C % 8 != 0 || 3 * a.C > a.K || !a.row_src || !a.row_flags) return hipErrorInvalidValue;
   switch (epi) {
-    case EPI_BIAS_GELU: return launch_shape<A_CONV3, EPI_BIAS_GELU>(a, s);
-    case EPI_BIAS_GELU_POS: return launch_shape<A_CONV3, EPI_BIAS_GELU_POS>(a, s);
+    case EPI_BIAS_GELU:
+      return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU>(a, s) : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU>(a, s);
+    case EPI_BIAS_GELU_POS:
+      if (!a.pos || !a.row_pos) return hipErrorInvalidValue;
+      return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s)
+                 : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -31,7 +31,6 @@ struct GemmArgs {
   void *out;                // [M, ldo]; bf16 for EPI_BIAS / EPI_BIAS_GELU on the MFMA path, else fp32
   int32_t M, N, K;          // K is the padded reduction length (multiple of 64 on the MFMA path)
   int32_t lda, ldo;
-  int32_t group_n;          // tile columns per column group of the tile order (set by the launcher)
   // A_CONV3 only
   const int32_t *row_src;
   const int32_t *row_flags;
