@@ -17,22 +17,25 @@ __device__ __forceinline__ float bf16_to_float(__bf16 v) { return (float)v; }
 // Exact-form GELU, z/2 (1 + erf(z / sqrt 2)), for the fp32 debug path.
 __device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
 
-// GELU for the bf16 path.  erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun
-// (|error| <= 1.5e-7, far below bf16 resolution): erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
-// t = 1/(1 + p x), x >= 0; odd extension for x < 0.
+// GELU for the bf16 path, z/2 (1 + erf(z / sqrt 2)), without transcendental instructions: its cost sits
+// in the GEMM epilogue while the matrix pipe idles.  erf(x) ~ x P(x^2) on [0, 2.8] with P a degree-7
+// near-minimax polynomial (|erf error| <= 7.5e-5), x clamped to 2.8 beyond (erf(2.8) = 0.99992).
+// Relative error of the result <= 4.7e-4 wherever |GELU| > 0.05, i.e. 8 times below the half-ulp of the
+// bf16 value it is rounded to; absolute error <= 1.5e-4 for |z| <= 4.
 __device__ __forceinline__ float gelu_fast(float z) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * x);
-  float poly = 1.061405429f;
-  poly = poly * t - 1.453152027f;
-  poly = poly * t + 1.421413741f;
-  poly = poly * t - 0.284496736f;
-  poly = poly * t + 0.254829592f;
-  poly *= t;
-  const float e = __expf(-x * x);
-  const float erf_abs = 1.0f - poly * e;         // erf(|z|/sqrt2)
-  const float erf_z = copysignf(erf_abs, z);
-  return 0.5f * z * (1.0f + erf_z);
+  const float az = fabsf(z);
+  const float x = fminf(az * 0.70710678118654752f, 2.8f);
+  const float t = x * x;
+  float p = -6.054487471e-07f;
+  p = p * t + 2.293834950e-05f;
+  p = p * t - 3.810082562e-04f;
+  p = p * t + 3.704522969e-03f;
+  p = p * t - 2.387478016e-02f;
+  p = p * t + 1.095759571e-01f;
+  p = p * t - 3.744913936e-01f;
+  p = p * t + 1.128137589e+00f;
+  const float e = x * p;                  // erf(|z| / sqrt 2)
+  return 0.5f * (z + az * e);             // z/2 + |z| erf(|z|/sqrt2)/2 = z/2 (1 + erf(z/sqrt2))
 }
 
 // First stream index i with cu[i+1] > r, for a row r in [0, cu[B]).

@@ -331,13 +331,19 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
       for (int j = 0; j < IN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
   };
-  // lgkmcnt(0) placed BEFORE the next reads are issued, so that it only waits for the older ones
-#define WF_STEP(stage, ks_next, buf_next, buf_cur)  \
-  __builtin_amdgcn_s_waitcnt(0xC07F);               \
-  __builtin_amdgcn_sched_barrier(0);                \
-  rd(stage, ks_next, buf_next);                     \
-  __builtin_amdgcn_sched_barrier(0);                \
-  mm(buf_cur);                                      \
+  // One k-step: lgkmcnt(0) is placed BEFORE the next reads are issued, so that it only waits for the
+  // older ones; then the scheduler is told to alternate one MFMA with one LDS read, which hides the
+  // issue slots of the reads under the matrix pipe's 32-cycle occupancy per MFMA.
+#define WF_STEP(stage, ks_next, buf_next, buf_cur)                                                     \
+  __builtin_amdgcn_s_waitcnt(0xC07F);                                                                 \
+  __builtin_amdgcn_sched_barrier(0);                                                                  \
+  rd(stage, ks_next, buf_next);                                                                       \
+  mm(buf_cur);                                                                                        \
+  _Pragma("unroll") for (int q_ = 0; q_ < IM + IN; ++q_) {                                            \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                \
+  }                                                                                                   \
+  __builtin_amdgcn_sched_group_barrier(0x008, IM * IN - (IM + IN), 0);                                \
   __builtin_amdgcn_sched_barrier(0)
 
   issue(0);
