@@ -216,8 +216,16 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
     attr_set = true;
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
-  const int grid = ((tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  GemmArgs b = a;
+  constexpr int kCUs = 256;
+  const int rest = tiles % kCUs;
+  const bool split = rest > 0 && 2 * rest <= kCUs;
+  b.n_full = split ? tiles - rest : tiles;
+  b.n_half = split ? 2 * rest : 0;
+  b.full_per_xcd = (b.n_full + 7) / 8;
+  b.half_per_xcd = (b.n_half + 7) / 8;
+  const int grid = 8 * (b.full_per_xcd + b.half_per_xcd);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
   return hipGetLastError();
 }
 
@@ -229,27 +237,18 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
+// One BM x BN output tile at (m0, n0), computed by the whole workgroup.
+template <int BM, int BN, int WM, int WN, int EPI, int SMEM>   // SMEM: bytes of LDS the kernel owns
+__device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int IM = TM / 32, IN = TN / 32;
   constexpr int XL = BM / 8 / NW;    // load instructions per wave for the activation tile (8 rows each)
   constexpr int WL = BN / 8 / NW;
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TN % 32 == 0, "tile/waves mismatch");
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char *sX = smem;                        // [2][BM][128 B]
   unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
-
-  const int tiles_m = (p.M + BM - 1) / BM;
-  const int tiles_n = p.N / BN;
-  const int n_tiles = tiles_m * tiles_n;
-  const int per_xcd = (n_tiles + 7) >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);   // XCD x runs tiles [x*per_xcd, (x+1)*per_xcd)
-  if (tile >= n_tiles) return;
-  const int m0 = (tile / tiles_n) * BM;
-  const int n0 = (tile % tiles_n) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -343,7 +342,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                \
   }                                                                                                   \
-  __builtin_amdgcn_sched_group_barrier(0x008, IM * IN - (IM + IN), 0);                                \
+  __builtin_amdgcn_sched_group_barrier(0x008, (IM * IN > IM + IN ? IM * IN - (IM + IN) : 0), 0);      \
   __builtin_amdgcn_sched_barrier(0)
 
   issue(0);
@@ -378,7 +377,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __builtin_amdgcn_s_barrier();                    // every wave is done reading the last K step
   unsigned char *stg = smem + wave * (TM * 256);   // TM rows x 256 bytes (<= 16 KB per wave)
-  static_assert(NW * TM * 256 <= 2 * (BM + BN) * 128, "staging does not fit in the LDS stages");
+  static_assert(NW * TM * 256 <= SMEM && 2 * (BM + BN) * 128 <= SMEM, "staging does not fit in the LDS stages");
   const int mw0 = m0 + wm * TM, nw0 = n0 + wn * TN;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
     constexpr int RB = TN * 2;                     // row bytes (bf16)
@@ -415,16 +414,17 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
       if (m < p.M) *(u32x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nw0 + c * 8) = v;
     }
   } else {
-    // fp32 residual update in place, 64 features (256 bytes per row) per pass
-    constexpr int CPR = 16;
+    // fp32 residual update in place, PW features (PW * 4 bytes per row) per pass
+    constexpr int PW = TN >= 64 ? 64 : TN;         // features per pass
+    constexpr int RB = PW * 4, CPR = RB / 16, RPI = 64 / CPR;
 #pragma unroll
-    for (int ps = 0; ps < TN / 64; ++ps) {
+    for (int ps = 0; ps < TN / PW; ++ps) {
 #pragma unroll
       for (int i = 0; i < IM; ++i) {
         const int r = i * 32 + l32;
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int j = ps * 2 + jj;
+        for (int jj = 0; jj < PW / 32; ++jj) {
+          const int j = ps * (PW / 32) + jj;
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const int nl = j * 32 + g * 8 + lg * 4;
@@ -432,20 +432,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
             f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
-            const int ch = (nl & 63) >> 2;         // 16-byte chunk inside the 64-feature pass
-            *(f32x4 *)(stg + r * 256 + ((ch ^ (r & (CPR - 1))) << 4)) = v;
+            const int ch = (nl % PW) >> 2;         // 16-byte chunk inside the pass
+            *(f32x4 *)(stg + r * RB + ((ch ^ (r & (CPR - 1))) << 4)) = v;
           }
         }
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);
-      const int rr = lane >> 4, c = lane & 15;
+      const int rr = lane / CPR, c = lane % CPR;
 #pragma unroll
-      for (int it = 0; it < TM / 4; ++it) {
-        const int r = it * 4 + rr;
-        const f32x4 v = *(const f32x4 *)(stg + r * 256 + ((c ^ (r & (CPR - 1))) << 4));
+      for (int it = 0; it < TM / RPI; ++it) {
+        const int r = it * RPI + rr;
+        const f32x4 v = *(const f32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
         const int m = mw0 + r;
         if (m < p.M) {
-          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * 64 + c * 4);
+          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
           f32x4 x = *o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) x[e] += v[e];
@@ -457,6 +457,28 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
   }
 }
 
+// Workgroup -> work unit.  Full BM x BN tiles first; when the tiles left over after the last full round
+// of the chip would occupy at most half of it, each of them is split into two BM x BN/2 units so that the
+// last round takes half as long (620 tiles on 256 CUs: 2.5 rounds instead of 3).  Consecutive workgroup
+// ids go to different XCDs; XCD x gets the full tiles [x*full_per_xcd, ...) and the half units
+// [x*half_per_xcd, ...), full tiles first.
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tiles_n = p.N / BN;
+  const int xcd = blockIdx.x & 7, l = blockIdx.x >> 3;
+  if (l < p.full_per_xcd) {
+    const int tile = xcd * p.full_per_xcd + l;
+    if (tile >= p.n_full) return;
+    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128>(p, smem, (tile / tiles_n) * BM, (tile % tiles_n) * BN);
+  } else {
+    const int hl = l - p.full_per_xcd;
+    const int h = xcd * p.half_per_xcd + hl;
+    if (hl >= p.half_per_xcd || h >= p.n_half) return;
+    const int tile = p.n_full + (h >> 1);
+    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128>(p, smem, (tile / tiles_n) * BM, (tile % tiles_n) * BN + (h & 1) * (BN / 2));
+  }
+}
 
 template <int BM, int BN, int WM, int WN, int EPI>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
@@ -469,8 +491,16 @@ hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
     attr_set = true;
   }
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
-  const int grid = ((tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+  GemmArgs b = a;
+  constexpr int kCUs = 256;
+  const int rest = tiles % kCUs;
+  const bool split = rest > 0 && 2 * rest <= kCUs;
+  b.n_full = split ? tiles - rest : tiles;
+  b.n_half = split ? 2 * rest : 0;
+  b.full_per_xcd = (b.n_full + 7) / 8;
+  b.half_per_xcd = (b.n_half + 7) / 8;
+  const int grid = 8 * (b.full_per_xcd + b.half_per_xcd);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
   return hipGetLastError();
 }
 

@@ -31,6 +31,8 @@ struct GemmArgs {
   void *out;                // [M, ldo]; bf16 for EPI_BIAS / EPI_BIAS_GELU on the MFMA path, else fp32
   int32_t M, N, K;          // K is the padded reduction length (multiple of 64 on the MFMA path)
   int32_t lda, ldo;
+  // work-unit split of the direct-load GEMM (set by its launcher): full tiles, then half-width units
+  int32_t n_full, n_half, full_per_xcd, half_per_xcd;
   // A_CONV3 only
   const int32_t *row_src;
   const int32_t *row_flags;
