@@ -151,6 +151,35 @@ def make_mels(shape: Shape, n_frames: List[int], seed: int,
     return out
 
 
+SAMPLE_RATE = 16000           # Section "Hush word", target level: raw audio is sampled at 16 kHz
+HUSH_SAMPLES = 8000           # Section "Key Implementation Details": the hush word is a 1-d tensor of shape (8000,)
+SAMPLES_PER_FRAME = SAMPLE_RATE // FRAMES_PER_SECOND
+
+
+def make_audio(n_samples: int, seed: int) -> np.ndarray:
+    """Seeded synthetic raw audio in [-1, 1]: a few tones with slow amplitude envelopes over white noise.
+    Stands in for the speech recordings of the paper's datasets (none of which is reproduced)."""
+    rng = np.random.default_rng(seed)
+    t = np.arange(n_samples, dtype=np.float64) / SAMPLE_RATE
+    x = 0.02 * rng.standard_normal(n_samples)
+    for _ in range(4):
+        f = rng.uniform(80.0, 3800.0)
+        a = rng.uniform(0.05, 0.25)
+        env = 0.5 * (1.0 + np.sin(2 * np.pi * rng.uniform(0.3, 3.0) * t + rng.uniform(0, 2 * np.pi)))
+        x += a * env * np.sin(2 * np.pi * f * t + rng.uniform(0, 2 * np.pi))
+    return np.clip(x, -1.0, 1.0).astype(np.float32)
+
+
+def make_audios(n_frames: List[int], seed: int) -> List[np.ndarray]:
+    """One raw-audio buffer per stream, n_frames[i] * 160 samples each."""
+    return [make_audio(t * SAMPLES_PER_FRAME, seed + 1000 + i) for i, t in enumerate(n_frames)]
+
+
+def make_hush_audio(seed: int, n_samples: int = HUSH_SAMPLES) -> np.ndarray:
+    """The fixed appended raw-audio segment (synthetic: the trained hush words are not available)."""
+    return make_audio(n_samples, seed + 500)
+
+
 def draw_lengths_uniform(n: int, lo_s: float, hi_s: float, seed: int) -> List[int]:
     u = np.random.default_rng(seed).random(n)
     return [int(round(FRAMES_PER_SECOND * (lo_s + (hi_s - lo_s) * x))) for x in u]
