@@ -63,6 +63,36 @@ def cpu_baseline(wl, weights, hush, mels, budget_flops=1.2e12):
                       f"NumPy fp64 oracle, {dt:.1f} s wall, {fl / dt / 1e9:.1f} GFLOP/s"}
 
 
+def bench_frontend(wl, n_frames, steps, warmup):
+    """Raw 16 kHz audio of the workload's lengths + the 8000-sample hush word -> packed log-mel (not part of `value`)."""
+    import numpy as np
+    import torch
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+    lens = [int(t) * synth.SAMPLES_PER_FRAME for t in n_frames]
+    audios = synth.make_audios([int(t) for t in n_frames], wl.seeds["mel"])
+    hush = synth.make_hush_audio(wl.seeds["hush"])
+    fe = wf.Frontend(wl.shape.n_mels, hush, len(lens), sum(lens) + len(lens) * len(hush))
+    audio = torch.from_numpy(np.concatenate(audios)).cuda()
+    offs = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    frames = sum(fe.n_frames(lens))
+    out = torch.empty((frames, wl.shape.n_mels), device="cuda", dtype=torch.float32)
+    for _ in range(warmup):
+        fe.logmel(audio, offs, lens, out=out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fe.logmel(audio, offs, lens, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    fe.close()
+    flops = frames * (2.0 * 2 * 400 * 201)                     # the DFT contraction; the mel filters are a few % of it
+    return {"ms": round(ms, 4), "frames": int(frames), "audio_s_per_s": round(sum(lens) / 16000.0 / (ms / 1e3), 1),
+            "dft_tflops": round(flops / ms / 1e9, 2), "peak_fp32_mfma_tflops": 157.3,
+            "frac": round(flops / ms / 1e9 / 157.3, 4), "dtype": "f32"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +100,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--frontend", action="store_true",
+                    help="also time the raw-audio log-mel front end on audio of the same lengths (reported separately)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -167,6 +199,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if args.frontend:
+        result["frontend"] = bench_frontend(wl, nf, args.steps, args.warmup)
     enc.close()
     del mel, out
     torch.cuda.empty_cache()

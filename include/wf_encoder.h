@@ -182,6 +182,40 @@ int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, 
 int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
                     int32_t n_heads, void *hip_stream);
 
+/*
+ * Log-mel front end with the hush word appended at the raw-audio level (the step right before the
+ * encoder).  Paper: raw audio is a 16 kHz one-dimensional array, 1 s of it is a (100, 80) log-mel matrix,
+ * and the hush word is a fixed raw-audio vector of 8000 samples placed at the end of the audio before the
+ * spectrogram is taken (Section "Hush word", position and target level; Section "Key Implementation
+ * Details").  Everything else is this library's reading: periodic Hann window of 400 samples, frames
+ * centred on multiples of 160 samples with 200 samples of reflect padding, 400-point DFT (201 bins),
+ * power spectrum, n_mels unit-peak triangular filters equally spaced on the mel scale
+ * 2595 log10(1 + f/700) over [0, 8000] Hz, log10 with floor 1e-10, clamp to within 8 decades of the
+ * stream's maximum, then (v + 4) / 4.  Stream i with N_i samples yields floor((N_i + H) / 160) frames.
+ *
+ * wf_frontend_create   hush_audio: HOST fp32 [hush_samples] (copied), may be NULL iff hush_samples == 0.
+ * wf_logmel_batch      audio_dev: DEVICE fp32 samples; sample_offset / n_samples: HOST [B] (first sample of
+ *                      stream i inside audio_dev, and N_i); mel_out_dev: DEVICE [sum T'_i, n_mels] packed
+ *                      stream-major, dtype mel_dtype (WF_DTYPE_*), directly usable as wf_encode_batch input
+ *                      (with an encoder created with hush_frames = 0); cu_frames_host: HOST [B+1], may be
+ *                      NULL.  Asynchronous on hip_stream.  WF_E_INVALID_ARG if N_i + H < 201 (shorter than
+ *                      the reflect padding) or N_i < 0; WF_E_CAPACITY beyond max_streams / max_total_samples
+ *                      (sum of N_i + H) / mel_capacity_frames.
+ */
+typedef struct wf_frontend wf_frontend;
+typedef struct {
+  int32_t n_mels;               /* 1 .. 256 */
+  int32_t hush_samples;         /* H >= 0 */
+  int32_t max_streams;
+  int64_t max_total_samples;    /* capacity: sum over streams of (N_i + H) */
+} wf_frontend_config;
+
+int wf_frontend_create(const wf_frontend_config *cfg, const float *hush_audio, wf_frontend **out);
+int wf_logmel_batch(wf_frontend *fe, const float *audio_dev, const int64_t *sample_offset, const int32_t *n_samples,
+                    int32_t B, void *mel_out_dev, int32_t mel_dtype, int64_t mel_capacity_frames,
+                    int32_t *cu_frames_host, void *hip_stream);
+void wf_frontend_destroy(wf_frontend *fe);
+
 #ifdef __cplusplus
 }
 #endif

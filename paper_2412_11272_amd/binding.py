@@ -45,6 +45,11 @@ class WfKernelStat(C.Structure):
                 ("bytes", C.c_double)]
 
 
+class WfFrontendConfig(C.Structure):
+    _fields_ = [("n_mels", C.c_int32), ("hush_samples", C.c_int32), ("max_streams", C.c_int32),
+                ("max_total_samples", C.c_int64)]
+
+
 class WfError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"wf error {code}: {msg}")
@@ -55,7 +60,8 @@ _lib = None
 
 EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_last_error", "wf_plan_batch",
            "wf_config_check", "wf_kernel_class_count", "wf_encoder_set_profiling", "wf_encoder_kernel_stats",
-           "wf_op_linear", "wf_op_layernorm", "wf_op_attention"]
+           "wf_op_linear", "wf_op_layernorm", "wf_op_attention",
+           "wf_frontend_create", "wf_logmel_batch", "wf_frontend_destroy"]
 
 
 def lib() -> C.CDLL:
@@ -84,6 +90,11 @@ def lib() -> C.CDLL:
     L.wf_op_layernorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_float, C.c_void_p]
     L.wf_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, _ip, C.c_int32, C.c_int32, C.c_void_p]
+    L.wf_frontend_create.argtypes = [C.POINTER(WfFrontendConfig), C.c_void_p, C.POINTER(C.c_void_p)]
+    L.wf_logmel_batch.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), _ip, C.c_int32, C.c_void_p, C.c_int32,
+                                  C.c_int64, _ip, C.c_void_p]
+    L.wf_frontend_destroy.argtypes = [C.c_void_p]
+    L.wf_frontend_destroy.restype = None
     _lib = L
     return L
 
@@ -177,6 +188,47 @@ class Encoder:
     def close(self):
         if self._h:
             lib().wf_encoder_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Frontend:
+    """Owns one wf_frontend: raw 16 kHz audio (+ hush word appended at the raw level) -> packed log-mel."""
+
+    def __init__(self, n_mels: int, hush_audio: Optional[np.ndarray], max_streams: int, max_total_samples: int):
+        h = None if hush_audio is None or len(hush_audio) == 0 else _f32(hush_audio)
+        self.cfg = WfFrontendConfig(n_mels, 0 if h is None else len(h), max_streams, max_total_samples)
+        self._h = C.c_void_p(None)
+        _check(lib().wf_frontend_create(C.byref(self.cfg), None if h is None else h.ctypes.data_as(C.c_void_p),
+                                        C.byref(self._h)))
+
+    def n_frames(self, n_samples: Sequence[int]) -> List[int]:
+        return [(int(n) + self.cfg.hush_samples) // 160 for n in n_samples]
+
+    def logmel(self, audio, sample_offset: Sequence[int], n_samples: Sequence[int], out=None, out_dtype=None, stream=None):
+        """audio: CUDA float32 tensor of samples.  Returns (mel [sum T', n_mels] CUDA tensor, cu_frames ndarray)."""
+        import torch
+        B = len(n_samples)
+        F = sum(self.n_frames(n_samples))
+        if out is None:
+            out = torch.empty((max(F, 1), self.cfg.n_mels), device=audio.device, dtype=out_dtype or torch.float32)[:F]
+        s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        off = np.ascontiguousarray(sample_offset, dtype=np.int64)
+        ns = np.ascontiguousarray(n_samples, dtype=np.int32)
+        cu = np.zeros(B + 1, dtype=np.int32)
+        _check(lib().wf_logmel_batch(self._h, C.c_void_p(audio.data_ptr()), off.ctypes.data_as(C.POINTER(C.c_int64)),
+                                     ns.ctypes.data_as(_ip), B, C.c_void_p(out.data_ptr() or out.untyped_storage().data_ptr()),
+                                     _torch_dtype_code(out.dtype), out.shape[0], cu.ctypes.data_as(_ip), C.c_void_p(s)))
+        return out, cu
+
+    def close(self):
+        if self._h:
+            lib().wf_frontend_destroy(self._h)
             self._h = C.c_void_p(None)
 
     def __del__(self):

@@ -32,6 +32,19 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
+}  // namespace
+
+namespace wf {
+// Same thread-local error text for every translation unit of the library.
+int set_error(int code, const char *fmt, va_list ap) {
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  return code;
+}
+char *error_buffer() { return g_err; }
+}  // namespace wf
+
+namespace {
+
 #define HIP_TRY(expr)                                                                         \
   do {                                                                                        \
     hipError_t e_ = (expr);                                                                   \

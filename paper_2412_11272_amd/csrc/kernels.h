@@ -2,6 +2,7 @@
 // Nothing here is part of the public ABI (include/wf_encoder.h is).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdarg.h>
 #include <stdint.h>
 
 namespace wf {
@@ -72,6 +73,10 @@ int attention_q_tile();     // query rows per attention work item
 // fp32 debug path ------------------------------------------------------------------------------
 hipError_t launch_gemm_f32(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t s);
+
+// thread-local error text behind wf_last_error(), shared by all translation units
+int set_error(int code, const char *fmt, va_list ap);
+char *error_buffer();
 
 // one-time per-process kernel attribute setup (dynamic LDS limits)
 hipError_t init_kernels();
