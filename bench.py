@@ -34,7 +34,7 @@ def algorithmic_flops(shape, hush_frames, n_frames):
     return total
 
 
-def cpu_baseline(wl, weights, hush, mels, budget_flops=1.2e12):
+def cpu_baseline(wl, weights, hush, mels, budget_flops=6e12):
     """The oracle as it stands, timed on a bounded sample of the workload's streams."""
     import numpy as np
     from oracle import encoder_oracle as O

@@ -180,6 +180,73 @@ def make_hush_audio(seed: int, n_samples: int = HUSH_SAMPLES) -> np.ndarray:
     return make_audio(n_samples, seed + 500)
 
 
+# ---- decoder side (cross-attention K/V projection and prompt prefill) -----------------------------
+
+@dataclass(frozen=True)
+class DecoderShape:
+    """Decoder architecture that goes with an encoder Shape of the same d_model."""
+    d_model: int
+    n_layers: int
+    n_heads: int
+    d_mlp: int
+    n_vocab: int
+    n_ctx: int          # rows of the learned position table
+
+
+DEC_SHAPES: Dict[str, DecoderShape] = {
+    "tiny": DecoderShape(384, 4, 6, 1536, 51865, 448),
+    "base": DecoderShape(512, 6, 8, 2048, 51865, 448),
+    "small": DecoderShape(768, 12, 12, 3072, 51865, 448),
+    "medium": DecoderShape(1024, 24, 16, 4096, 51865, 448),
+    "large-v3": DecoderShape(1280, 32, 20, 5120, 51866, 448),
+    "unit": DecoderShape(128, 2, 2, 256, 1000, 160),
+}
+PROMPT_TOKENS = 100          # Section "CPU/GPU pipelining", categorization of workloads: ~100 prompt tokens
+
+
+def make_decoder_weights(shape: DecoderShape, seed: int, q_scale: float = 1.0, affine_random: bool = False) -> dict:
+    """Matrices, embeddings and biases ~ N(0, 0.02); LayerNorm gain 1 / shift 0 unless affine_random.
+    Linear weights are [out, in].  Self-attention: wq bq wk wv bv wo bo; cross-attention: xwq xbq xwk
+    xwv xbv xwo xbo (key projections carry no bias)."""
+    rng = np.random.default_rng(seed)
+    d, f = shape.d_model, shape.d_mlp
+
+    def n(*s):
+        return rng.normal(0.0, WEIGHT_STD, size=s).astype(np.float32)
+
+    def gain():
+        return (1.0 + 0.2 * rng.standard_normal(d)).astype(np.float32) if affine_random else np.ones(d, np.float32)
+
+    def shift():
+        return (0.1 * rng.standard_normal(d)).astype(np.float32) if affine_random else np.zeros(d, np.float32)
+
+    w = {"tok_emb": n(shape.n_vocab, d), "pos_emb": n(shape.n_ctx, d), "layers": []}
+    qs = np.float32(q_scale)
+    for _ in range(shape.n_layers):
+        w["layers"].append({
+            "ln1_g": gain(), "ln1_b": shift(),
+            "wq": n(d, d) * qs, "bq": n(d) * qs, "wk": n(d, d) * qs, "wv": n(d, d), "bv": n(d), "wo": n(d, d), "bo": n(d),
+            "lnx_g": gain(), "lnx_b": shift(),
+            "xwq": n(d, d) * qs, "xbq": n(d) * qs, "xwk": n(d, d) * qs, "xwv": n(d, d), "xbv": n(d), "xwo": n(d, d), "xbo": n(d),
+            "ln2_g": gain(), "ln2_b": shift(),
+            "w1": n(f, d), "b1": n(f), "w2": n(d, f), "b2": n(d),
+        })
+    w["lnf_g"], w["lnf_b"] = gain(), shift()
+    return w
+
+
+def make_prompts(lengths: List[int], n_vocab: int, seed: int) -> List[np.ndarray]:
+    """Uniformly drawn token ids, one int32 array per stream."""
+    rng = np.random.default_rng(seed)
+    return [rng.integers(0, n_vocab, size=int(p), dtype=np.int64).astype(np.int32) for p in lengths]
+
+
+def make_enc_states(n_tokens: int, d_model: int, seed: int) -> np.ndarray:
+    """Stand-in encoder states for decoder-only tests: unit normal, like rows after a LayerNorm."""
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((n_tokens, d_model)).astype(np.float32)
+
+
 def draw_lengths_uniform(n: int, lo_s: float, hi_s: float, seed: int) -> List[int]:
     u = np.random.default_rng(seed).random(n)
     return [int(round(FRAMES_PER_SECOND * (lo_s + (hi_s - lo_s) * x))) for x in u]
