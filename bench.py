@@ -93,6 +93,55 @@ def bench_frontend(wl, n_frames, steps, warmup):
             "frac": round(flops / ms / 1e9 / 157.3, 4), "dtype": "f32"}
 
 
+def bench_prefill(wl, states, cu, steps, warmup):
+    """Decoder-side consumers of the encoder states of the same batch: per-layer cross-attention K/V
+    projection, then ~100 prompt tokens per stream through the decoder (reported separately, not part of `value`)."""
+    import numpy as np
+    import torch
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+    name = next(k for k, v in synth.SHAPES.items() if v == wl.shape)
+    shape = synth.DEC_SHAPES[name]
+    B, M, P = len(cu) - 1, int(cu[-1]), synth.PROMPT_TOKENS
+    w = synth.make_decoder_weights(shape, wl.seeds["weights"] + 6)
+    prompts = synth.make_prompts([P] * B, shape.n_vocab, wl.seeds["weights"] + 7)
+    dec = wf.Decoder(shape, w, B, M, P * B, wf.WF_PRECISION_BF16)
+    del w
+    kv = torch.empty((shape.n_layers, M, 2 * shape.d_model), device="cuda", dtype=torch.bfloat16)
+    hidden = torch.empty((P * B, shape.d_model), device="cuda", dtype=torch.bfloat16)
+    logits = torch.empty((B, shape.n_vocab), device="cuda", dtype=torch.float32)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms_kv = timed(lambda: dec.cross_kv(states, out=kv))
+    ms_pf = timed(lambda: dec.prefill(prompts, cu, kv, hidden=hidden, logits=logits))
+    dec.set_profiling(True)
+    dec.cross_kv(states, out=kv)
+    dec.prefill(prompts, cu, kv, hidden=hidden, logits=logits)
+    torch.cuda.synchronize()
+    stats = dec.kernel_stats()
+    dec.close()
+    d, f, N = shape.d_model, shape.d_mlp, shape.n_layers
+    fl_kv = 2.0 * M * d * 2 * d * N
+    Pt = P * B
+    fl_pf = N * (2.0 * Pt * d * (3 * d + d + d + d + 2 * f) + 2.0 * B * P * (P + 1) * d + 4.0 * P * M * d) + 2.0 * B * d * shape.n_vocab
+    kern = {s["name"]: {"launches": s["launches"], "avg_ms": round(s["total_ms"] / s["launches"], 4),
+                        "tflops": round(s["flops"] / s["total_ms"] / 1e9, 1) if s["flops"] else None}
+            for s in stats if s["launches"]}
+    return {"decoder": f"{name}: {N} layers, {P} prompt tokens x {B} streams, {M} encoder tokens",
+            "cross_kv_ms": round(ms_kv, 3), "cross_kv_tflops": round(fl_kv / ms_kv / 1e9, 1),
+            "prefill_ms": round(ms_pf, 3), "prefill_tflops": round(fl_pf / ms_pf / 1e9, 1), "dtype": "bf16", "kernels": kern}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +151,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the raw-audio log-mel front end on audio of the same lengths (reported separately)")
+    ap.add_argument("--prefill", action="store_true",
+                    help="also time the decoder-side steps on the encoder states of the same batch (reported separately)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -202,6 +253,8 @@ def main():
     if args.frontend:
         result["frontend"] = bench_frontend(wl, nf, args.steps, args.warmup)
     enc.close()
+    if args.prefill:
+        result["prefill"] = bench_prefill(wl, out, cu, args.steps, args.warmup)
     del mel, out
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -216,6 +216,74 @@ int wf_logmel_batch(wf_frontend *fe, const float *audio_dev, const int64_t *samp
                     int32_t *cu_frames_host, void *hip_stream);
 void wf_frontend_destroy(wf_frontend *fe);
 
+/* ---- Decoder-side consumers of the encoder states ---------------------------------------------------
+ * The two dense steps that follow the encoder in a processing round and stay on the GPU (paper Section
+ * "Operations", workload mapping; Section "CPU/GPU pipelining", categorization of workloads, item (2):
+ * about 100 prompt tokens pass through the decoder in one parallel pass):
+ *   wf_cross_kv   every decoder layer projects the packed encoder states once into the keys and values
+ *                 its cross-attention reads for the rest of the round: K_l = E Wk_l^T, V_l = E Wv_l^T + bv_l;
+ *   wf_prefill    the prompt tokens of every stream go through the decoder stack in one pass: token
+ *                 embedding + learned position, then per layer LayerNorm -> causal self-attention ->
+ *                 residual, LayerNorm -> cross-attention over that stream's encoder tokens -> residual,
+ *                 LayerNorm -> GELU MLP -> residual; final LayerNorm; logits of each stream's last prompt
+ *                 position against the (tied) token-embedding matrix.
+ * The decoder internals are not spelled out in the paper; this is the standard pre-LN encoder-decoder
+ * transformer matching the encoder above (key projections without bias, softmax scale 1/8, exact GELU).
+ *
+ * Layouts.  Element type "act" is bf16 for WF_PRECISION_BF16 and fp32 for WF_PRECISION_F32.
+ *   enc_dev        DEVICE [M, d_model] act, packed stream-major as wf_encode_batch writes it;
+ *   cu_seqlens     HOST [B+1] encoder-token prefix sums (cu_seqlens[0] == 0, every stream >= 1 token);
+ *   cross_kv_dev   DEVICE act, caller-owned: layer l occupies [kv_capacity_tokens, 2 d_model] starting at
+ *                  element l * kv_capacity_tokens * 2 d_model; row m = key (first d_model) | value of token m;
+ *   tokens         HOST int32 [sum P_i] prompt token ids, stream-major; cu_prompt HOST [B+1] prefix sums
+ *                  (1 <= P_i <= n_ctx, ids in [0, n_vocab));
+ *   hidden_out_dev DEVICE [sum P_i, d_model], dtype hidden_dtype (WF_DTYPE_*), may be NULL;
+ *   logits_out_dev DEVICE fp32 [B, n_vocab], may be NULL;
+ *   self_kv_out_dev DEVICE act, may be NULL: layer l occupies [self_kv_capacity_tokens, 2 d_model] like
+ *                  cross_kv_dev, row r = self-attention key | value of prompt token r (what token-by-token
+ *                  decoding continues from).
+ * Weights: HOST fp32 row-major [out, in], copied (and converted) at create.  All calls are asynchronous on
+ * hip_stream; one decoder object is not re-entrant.  Errors: WF_E_INVALID_ARG (NULL, bad lengths or ids,
+ * d_model/n_heads != 64), WF_E_CAPACITY (max_streams, max_enc_tokens, max_prompt_tokens, a caller capacity).
+ */
+typedef struct wf_decoder wf_decoder;
+typedef struct {
+  int32_t d_model, n_layers, n_heads, d_mlp, n_vocab, n_ctx;
+  int32_t max_streams;
+  int32_t max_enc_tokens;       /* capacity: total encoder tokens per call */
+  int32_t max_prompt_tokens;    /* capacity: total prompt tokens per call */
+  int32_t precision;            /* WF_PRECISION_* */
+  float ln_eps;                 /* <= 0 selects 1e-5 */
+} wf_decoder_config;
+
+typedef struct {
+  const float *ln1_g, *ln1_b;                         /* before self-attention */
+  const float *wq, *bq, *wk, *wv, *bv, *wo, *bo;      /* self-attention, [d, d] each */
+  const float *lnx_g, *lnx_b;                         /* before cross-attention */
+  const float *xwq, *xbq, *xwk, *xwv, *xbv, *xwo, *xbo;
+  const float *ln2_g, *ln2_b;                         /* before the MLP */
+  const float *w1 /* [d_mlp, d] */, *b1, *w2 /* [d, d_mlp] */, *b2;
+} wf_decoder_layer_weights;
+
+typedef struct {
+  const float *tok_emb;         /* [n_vocab, d_model] */
+  const float *pos_emb;         /* [n_ctx, d_model] */
+  const wf_decoder_layer_weights *layers;   /* [n_layers] */
+  const float *lnf_g, *lnf_b;
+} wf_decoder_weights;
+
+int wf_decoder_config_check(const wf_decoder_config *cfg);
+int wf_decoder_create(const wf_decoder_config *cfg, const wf_decoder_weights *w, wf_decoder **out);
+int wf_cross_kv(wf_decoder *dec, const void *enc_dev, int32_t M, void *cross_kv_dev, int64_t kv_capacity_tokens,
+                void *hip_stream);
+int wf_prefill(wf_decoder *dec, const int32_t *tokens, const int32_t *cu_prompt, const int32_t *cu_seqlens, int32_t B,
+               const void *cross_kv_dev, int64_t kv_capacity_tokens, void *hidden_out_dev, int32_t hidden_dtype,
+               float *logits_out_dev, void *self_kv_out_dev, int64_t self_kv_capacity_tokens, void *hip_stream);
+void wf_decoder_destroy(wf_decoder *dec);          /* NULL-safe */
+int wf_decoder_kernel_class_count(void);
+int wf_decoder_set_profiling(wf_decoder *dec, int32_t enabled);
+int wf_decoder_kernel_stats(wf_decoder *dec, wf_kernel_stat *stats, int32_t n_stats);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,24 @@ class WfFrontendConfig(C.Structure):
                 ("max_total_samples", C.c_int64)]
 
 
+class WfDecoderConfig(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("d_mlp", C.c_int32),
+                ("n_vocab", C.c_int32), ("n_ctx", C.c_int32), ("max_streams", C.c_int32), ("max_enc_tokens", C.c_int32),
+                ("max_prompt_tokens", C.c_int32), ("precision", C.c_int32), ("ln_eps", C.c_float)]
+
+
+_DEC_LAYER_FIELDS = ["ln1_g", "ln1_b", "wq", "bq", "wk", "wv", "bv", "wo", "bo", "lnx_g", "lnx_b", "xwq", "xbq", "xwk", "xwv",
+                     "xbv", "xwo", "xbo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"]
+
+
+class WfDecoderLayerWeights(C.Structure):
+    _fields_ = [(n, _fp) for n in _DEC_LAYER_FIELDS]
+
+
+class WfDecoderWeights(C.Structure):
+    _fields_ = [("tok_emb", _fp), ("pos_emb", _fp), ("layers", C.POINTER(WfDecoderLayerWeights)), ("lnf_g", _fp), ("lnf_b", _fp)]
+
+
 class WfError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"wf error {code}: {msg}")
@@ -61,7 +79,9 @@ _lib = None
 EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_last_error", "wf_plan_batch",
            "wf_config_check", "wf_kernel_class_count", "wf_encoder_set_profiling", "wf_encoder_kernel_stats",
            "wf_op_linear", "wf_op_layernorm", "wf_op_attention",
-           "wf_frontend_create", "wf_logmel_batch", "wf_frontend_destroy"]
+           "wf_frontend_create", "wf_logmel_batch", "wf_frontend_destroy",
+           "wf_decoder_config_check", "wf_decoder_create", "wf_cross_kv", "wf_prefill", "wf_decoder_destroy",
+           "wf_decoder_kernel_class_count", "wf_decoder_set_profiling", "wf_decoder_kernel_stats"]
 
 
 def lib() -> C.CDLL:
@@ -95,6 +115,15 @@ def lib() -> C.CDLL:
                                   C.c_int64, _ip, C.c_void_p]
     L.wf_frontend_destroy.argtypes = [C.c_void_p]
     L.wf_frontend_destroy.restype = None
+    L.wf_decoder_config_check.argtypes = [C.POINTER(WfDecoderConfig)]
+    L.wf_decoder_create.argtypes = [C.POINTER(WfDecoderConfig), C.POINTER(WfDecoderWeights), C.POINTER(C.c_void_p)]
+    L.wf_cross_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+    L.wf_prefill.argtypes = [C.c_void_p, _ip, _ip, _ip, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
+                             C.c_void_p, C.c_int64, C.c_void_p]
+    L.wf_decoder_destroy.argtypes = [C.c_void_p]
+    L.wf_decoder_destroy.restype = None
+    L.wf_decoder_set_profiling.argtypes = [C.c_void_p, C.c_int32]
+    L.wf_decoder_kernel_stats.argtypes = [C.c_void_p, C.POINTER(WfKernelStat), C.c_int32]
     _lib = L
     return L
 
@@ -229,6 +258,99 @@ class Frontend:
     def close(self):
         if self._h:
             lib().wf_frontend_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Decoder:
+    """Owns one wf_decoder: cross-attention K/V projection of the encoder states and prompt prefill.
+    weights: the dict layout of synth.make_decoder_weights (host fp32 arrays)."""
+
+    def __init__(self, shape, weights: dict, max_streams: int, max_enc_tokens: int, max_prompt_tokens: int,
+                 precision: int = WF_PRECISION_BF16, ln_eps: float = 1e-5):
+        self.cfg = WfDecoderConfig(shape.d_model, shape.n_layers, shape.n_heads, shape.d_mlp, shape.n_vocab, shape.n_ctx,
+                                   max_streams, max_enc_tokens, max_prompt_tokens, precision, ln_eps)
+        self._h = C.c_void_p(None)
+        keep: List[np.ndarray] = []
+
+        def p(a):
+            if a is None:
+                return None
+            a = _f32(a)
+            keep.append(a)
+            return a.ctypes.data_as(_fp)
+
+        n_layers = len(weights["layers"])
+        layers = (WfDecoderLayerWeights * max(n_layers, 1))()
+        for i, lw in enumerate(weights["layers"]):
+            for name in _DEC_LAYER_FIELDS:
+                setattr(layers[i], name, p(lw.get(name)))
+        w = WfDecoderWeights(p(weights["tok_emb"]), p(weights["pos_emb"]), layers, p(weights["lnf_g"]), p(weights["lnf_b"]))
+        _check(lib().wf_decoder_create(C.byref(self.cfg), C.byref(w), C.byref(self._h)))
+
+    @property
+    def act_dtype(self):
+        import torch
+        return torch.bfloat16 if self.cfg.precision == WF_PRECISION_BF16 else torch.float32
+
+    def cross_kv(self, enc, out=None, stream=None):
+        """enc: CUDA [M, d] in the activation dtype.  Returns [n_layers, M, 2 d] (keys | values)."""
+        import torch
+        M = enc.shape[0]
+        if out is None:
+            out = torch.empty((self.cfg.n_layers, max(M, 1), 2 * self.cfg.d_model), device=enc.device, dtype=self.act_dtype)
+        s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        _check(lib().wf_cross_kv(self._h, C.c_void_p(enc.data_ptr()), M, C.c_void_p(out.data_ptr()), out.shape[1], C.c_void_p(s)))
+        return out
+
+    def prefill(self, prompts: Sequence[Sequence[int]], cu_seqlens: Sequence[int], cross_kv, hidden_dtype=None,
+                want_logits: bool = True, want_self_kv: bool = False, hidden=None, logits=None, self_kv=None, stream=None):
+        """prompts: per-stream token ids (host).  cross_kv: what cross_kv() returned for the same batch.
+        Returns dict(hidden [sum P, d], logits [B, n_vocab] fp32, self_kv [n_layers, sum P, 2 d], cu_prompt)."""
+        import torch
+        B = len(prompts)
+        lens = [len(p) for p in prompts]
+        cup = np.zeros(B + 1, dtype=np.int32)
+        cup[1:] = np.cumsum(lens)
+        Pt = int(cup[-1])
+        tok = np.ascontiguousarray(np.concatenate([np.asarray(p, dtype=np.int32) for p in prompts]) if Pt else np.zeros(1, np.int32))
+        cus = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+        dev = cross_kv.device
+        if hidden is None and hidden_dtype is not None:
+            hidden = torch.empty((max(Pt, 1), self.cfg.d_model), device=dev, dtype=hidden_dtype)
+        if logits is None and want_logits:
+            logits = torch.empty((max(B, 1), self.cfg.n_vocab), device=dev, dtype=torch.float32)
+        if self_kv is None and want_self_kv:
+            self_kv = torch.empty((self.cfg.n_layers, max(Pt, 1), 2 * self.cfg.d_model), device=dev, dtype=self.act_dtype)
+        s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        _check(lib().wf_prefill(self._h, tok.ctypes.data_as(_ip), cup.ctypes.data_as(_ip), cus.ctypes.data_as(_ip), B,
+                                C.c_void_p(cross_kv.data_ptr()), cross_kv.shape[1],
+                                C.c_void_p(hidden.data_ptr()) if hidden is not None else None,
+                                _torch_dtype_code(hidden.dtype) if hidden is not None else 0,
+                                C.c_void_p(logits.data_ptr()) if logits is not None else None,
+                                C.c_void_p(self_kv.data_ptr()) if self_kv is not None else None,
+                                self_kv.shape[1] if self_kv is not None else 0, C.c_void_p(s)))
+        return {"hidden": hidden[:Pt] if hidden is not None else None, "logits": logits[:B] if logits is not None else None,
+                "self_kv": self_kv, "cu_prompt": cup}
+
+    def set_profiling(self, on: bool):
+        _check(lib().wf_decoder_set_profiling(self._h, 1 if on else 0))
+
+    def kernel_stats(self) -> List[dict]:
+        n = lib().wf_decoder_kernel_class_count()
+        st = (WfKernelStat * n)()
+        _check(lib().wf_decoder_kernel_stats(self._h, st, n))
+        return [{"name": s.name.decode(), "launches": s.launches, "total_ms": s.total_ms, "flops": s.flops, "bytes": s.bytes}
+                for s in st]
+
+    def close(self):
+        if self._h:
+            lib().wf_decoder_destroy(self._h)
             self._h = C.c_void_p(None)
 
     def __del__(self):

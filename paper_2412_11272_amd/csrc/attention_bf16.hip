@@ -38,6 +38,12 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // consecutive elements, and lane i receives element i % 4 of the segments addressed by lanes
 // i/4, i/4 + 4, i/4 + 8, i/4 + 12.  Pointing lane r = a + 4e at (key K0 + e, features F0 + 4a ..) gives lane i
 // the four keys K0..K0+3 of feature F0 + i: four consecutive reduction indices of one V^T row.
+//
+// CAUSAL (self-attention among the prompt tokens of a decoder): query r sees keys 0..r.  Tiles that lie
+// wholly in the future of a work item are never loaded, a wave skips the tiles that lie wholly in the
+// future of its 32 queries (tile starts and wave starts are multiples of 32, so every tile a wave does
+// process holds at least one visible key for each of its queries).
+template <bool CAUSAL>
 __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   __shared__ __attribute__((aligned(1024))) unsigned char sK[2][BKV * 128];
   __shared__ __attribute__((aligned(1024))) unsigned char sV[2][BKV * 128];
@@ -46,29 +52,30 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   const int head = blockIdx.x % p.n_heads;
   const int stream = p.work[2 * item];
   const int q0 = p.work[2 * item + 1];
-  const int tok0 = p.cu_seqlens[stream];
-  const int L = p.cu_seqlens[stream + 1] - tok0;
+  const int tok0 = p.cu_q[stream];
+  const int Lq = p.cu_q[stream + 1] - tok0;
+  const int ktok0 = p.cu_kv[stream];
+  const int L = p.cu_kv[stream + 1] - ktok0;     // keys of this stream
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lg = lane >> 5;
-  const int ld = 3 * p.d_model;
-  const __bf16 *qkv = (const __bf16 *)p.qkv;
-  const __bf16 *Qb = qkv + (size_t)tok0 * ld + head * 64;
-  const __bf16 *Kb = Qb + p.d_model;
-  const __bf16 *Vb = Qb + 2 * p.d_model;
+  const int ldq = p.ldq, ld = p.ldkv;
+  const __bf16 *Qb = (const __bf16 *)p.q + (size_t)tok0 * ldq + head * 64;
+  const __bf16 *Kb = (const __bf16 *)p.k + (size_t)ktok0 * ld + head * 64;
+  const __bf16 *Vb = (const __bf16 *)p.v + (size_t)ktok0 * ld + head * 64;
 
   const int qw0 = q0 + wave * 32;              // first query of this wave
-  const bool wave_active = qw0 < L;            // waves past the end still help with the loads
+  const bool wave_active = qw0 < Lq;           // waves past the end still help with the loads
   int qrow = qw0 + l32;
-  const bool q_valid = qrow < L;
-  qrow = q_valid ? qrow : L - 1;
+  const bool q_valid = qrow < Lq;
+  qrow = q_valid ? qrow : Lq - 1;
 
   // Q fragments for the whole loop: features 16*ks + 8*lg + (0..7) of this lane's query.
   bf16x8 qf[4];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(Qb + (size_t)qrow * ld + ks * 16 + lg * 8);
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(Qb + (size_t)qrow * ldq + ks * 16 + lg * 8);
 
   f32x16 o[2];
 #pragma unroll
@@ -101,7 +108,8 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   const int tr_key = r16 >> 2;                           // e
   const int tr_feat = ((lane >> 4) & 1) * 16 + (r16 & 3) * 4;   // feature offset inside a 32-feature block
 
-  const int n_tiles = (L + BKV - 1) / BKV;
+  const int k_end = CAUSAL ? min(L, q0 + BQ) : L;          // keys this work item can see at all
+  const int n_tiles = (k_end + BKV - 1) / BKV;
   issue(0);
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int key0 = kt * BKV;
@@ -109,6 +117,7 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
     __builtin_amdgcn_s_barrier();               // everyone's has; the other buffer is no longer being read
     if (kt + 1 < n_tiles) issue(kt + 1);
     if (!wave_active) continue;
+    if (CAUSAL && key0 > qw0 + 31) continue;
     const unsigned char *cK = sK[kt & 1], *cV = sV[kt & 1];
 
     // ---- S^T = K Q^T : two 32-key blocks, reduction over the 64 features in 4 steps
@@ -132,6 +141,15 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
         for (int r = 0; r < 16; ++r) {
           const int key = key0 + kb2 * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
           if (key >= L) s[kb2][r] = -INFINITY;
+        }
+    }
+    if (CAUSAL && key0 + BKV - 1 > qw0) {
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kb2 * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+          if (key > qrow) s[kb2][r] = -INFINITY;
         }
     }
     float tmax = s[0][0];
@@ -216,7 +234,13 @@ int attention_q_tile() { return BQ; }
 hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.d_model != a.n_heads * 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attention_bf16_kernel, dim3(a.n_work * a.n_heads), dim3(256), 0, s, a);
+  if (a.ldq % 8 != 0 || a.ldkv % 8 != 0 || !a.q || !a.k || !a.v || !a.cu_q || !a.cu_kv) return hipErrorInvalidValue;
+  if (a.causal) {
+    if (a.cu_q != a.cu_kv) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attention_bf16_kernel<true>, dim3(a.n_work * a.n_heads), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(attention_bf16_kernel<false>, dim3(a.n_work * a.n_heads), dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -67,6 +67,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs p) {
       if (EPI == EPI_BIAS) *o = v;
       else if (EPI == EPI_BIAS_GELU) *o = gelu_erf(v);
       else if (EPI == EPI_BIAS_RESID) *o += v;
+      else if (EPI == EPI_BIAS_F32) *o = v;
       else *o = gelu_erf(v) + p.pos[(size_t)p.row_pos[m] * p.N + n];
     }
   }
@@ -81,16 +82,16 @@ __global__ void __launch_bounds__(256) attention_f32_kernel(AttnArgs p) {
   const int head = blockIdx.y;
   const bool active = m < p.M;
   const int mm = active ? m : p.M - 1;
-  const int i = find_stream(p.cu_seqlens, p.B, mm);
-  const int tok0 = p.cu_seqlens[i];
-  const int L = p.cu_seqlens[i + 1] - tok0;
-  const int ld = 3 * p.d_model;
-  const float *qkv = (const float *)p.qkv;
-  sQ[wave][lane] = qkv[(size_t)mm * ld + head * 64 + lane];
+  const int i = find_stream(p.cu_q, p.B, mm);
+  const int tok0 = p.cu_kv[i];
+  const int ld = p.ldkv;
+  // causal: query at position r of its stream sees keys 0..r
+  const int L = p.causal ? mm - p.cu_q[i] + 1 : p.cu_kv[i + 1] - tok0;
+  sQ[wave][lane] = ((const float *)p.q)[(size_t)mm * p.ldq + head * 64 + lane];
   __syncthreads();
   if (!active) return;
-  const float *Kb = qkv + (size_t)tok0 * ld + p.d_model + head * 64;
-  const float *Vb = Kb + p.d_model;
+  const float *Kb = (const float *)p.k + (size_t)tok0 * ld + head * 64;
+  const float *Vb = (const float *)p.v + (size_t)tok0 * ld + head * 64;
   float m_run = -INFINITY, l_run = 0.0f, o = 0.0f;
   for (int k0 = 0; k0 < L; k0 += 64) {
     const int key = k0 + lane;
@@ -139,6 +140,7 @@ hipError_t launch_gemm_f32(const GemmArgs &a, AMode amode, Epilogue epi, hipStre
       case EPI_BIAS: return launch_f32<A_PLAIN, EPI_BIAS>(a, s);
       case EPI_BIAS_GELU: return launch_f32<A_PLAIN, EPI_BIAS_GELU>(a, s);
       case EPI_BIAS_RESID: return launch_f32<A_PLAIN, EPI_BIAS_RESID>(a, s);
+      case EPI_BIAS_F32: return launch_f32<A_PLAIN, EPI_BIAS_F32>(a, s);
       default: return hipErrorInvalidValue;
     }
   }
@@ -151,6 +153,7 @@ hipError_t launch_gemm_f32(const GemmArgs &a, AMode amode, Epilogue epi, hipStre
 
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
+  if (!a.q || !a.k || !a.v || !a.cu_q || !a.cu_kv || (a.causal && a.cu_q != a.cu_kv)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(attention_f32_kernel, dim3((a.M + 3) / 4, a.n_heads), dim3(256), 0, s, a);
   return hipGetLastError();
 }

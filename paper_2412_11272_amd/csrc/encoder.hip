@@ -2,36 +2,18 @@
 // planner (prefix sums, attention work list) and the launch sequence behind the C ABI declared in
 // include/wf_encoder.h.  Everything device-side is in the kernel files; this file only sequences
 // them on the caller's stream.
-#include "../../include/wf_encoder.h"
+#include "host_runtime.h"
 
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
 #include <cmath>
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
 #include <new>
-#include <vector>
-
-#include "kernels.h"
 
 using namespace wf;
+using namespace wf::host;
 
 // ------------------------------------------------------------------------------------------------
 // errors
 namespace {
-
 thread_local char g_err[512] = "";
-
-int fail(int code, const char *fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_err, sizeof(g_err), fmt, ap);
-  va_end(ap);
-  return code;
-}
-
 }  // namespace
 
 namespace wf {
@@ -43,25 +25,9 @@ int set_error(int code, const char *fmt, va_list ap) {
 char *error_buffer() { return g_err; }
 }  // namespace wf
 
+#define HIP_TRY WF_HIP_TRY
+
 namespace {
-
-#define HIP_TRY(expr)                                                                         \
-  do {                                                                                        \
-    hipError_t e_ = (expr);                                                                   \
-    if (e_ != hipSuccess) return fail(e_ == hipErrorOutOfMemory ? WF_E_OOM : WF_E_HIP,        \
-                                      "%s: %s", #expr, hipGetErrorString(e_));                \
-  } while (0)
-
-inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
-
-// float -> bf16 bits, round to nearest even (NaN kept quiet).
-inline uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u;
-  memcpy(&u, &f, 4);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 enum KClass : int {
   KC_PREP = 0, KC_CONV1, KC_CONV2, KC_LN, KC_QKV, KC_ATTN, KC_OUT, KC_FC1, KC_FC2, KC_LNF, KC_COUNT
@@ -76,20 +42,12 @@ struct LayerDev {
   float *bqkv, *bo, *b1, *b2;
 };
 
-struct ProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
-
-constexpr int kStagingSlots = 4;
-
 }  // namespace
 
-struct wf_encoder {
+struct wf_encoder : DevCtx {
   wf_config cfg{};
-  int device = 0;
-  bool bf16 = true;
-  int es = 2;                           // bytes per activation/weight element
   int k1p = 0;                          // padded reduction length of the first convolution
   int64_t max_tokens = 0, max_work = 0, max_pos = 0;
-  std::vector<void *> allocs;           // every device allocation, for destroy
   // weights
   void *conv1_w = nullptr, *conv2_w = nullptr, *hush = nullptr;
   float *conv1_b = nullptr, *conv2_b = nullptr, *lnf_g = nullptr, *lnf_b = nullptr, *pos = nullptr;
@@ -100,52 +58,9 @@ struct wf_encoder {
   int32_t *frame_src = nullptr, *frame_flags = nullptr, *tok_src = nullptr, *tok_flags = nullptr, *tok_pos = nullptr;
   int32_t *idx_dev = nullptr;
   int64_t idx_ints = 0;
-  // pinned staging ring for the small per-call index arrays
-  int32_t *stage_host[kStagingSlots] = {};
-  hipEvent_t stage_evt[kStagingSlots] = {};
-  bool stage_used[kStagingSlots] = {};
-  int stage_next = 0;
-  // profiling
-  bool profiling = false;
-  std::vector<ProfRec> prof;
-  std::vector<hipEvent_t> evt_pool;
 };
 
 namespace {
-
-int dev_alloc(wf_encoder *e, void **p, size_t bytes) {
-  *p = nullptr;
-  if (bytes == 0) bytes = 256;
-  hipError_t err = hipMalloc(p, bytes);
-  if (err != hipSuccess) {
-    (void)hipGetLastError();
-    return fail(WF_E_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(err));
-  }
-  e->allocs.push_back(*p);
-  return WF_OK;
-}
-
-// Upload n floats as fp32.
-int upload_f32(wf_encoder *e, float **dst, const float *src, size_t n) {
-  int rc = dev_alloc(e, (void **)dst, n * 4);
-  if (rc) return rc;
-  HIP_TRY(hipMemcpy(*dst, src, n * 4, hipMemcpyHostToDevice));
-  return WF_OK;
-}
-
-// Upload a host fp32 matrix in the encoder's weight dtype (bf16 RNE or fp32).
-int upload_w(wf_encoder *e, void **dst, const std::vector<float> &src) {
-  int rc = dev_alloc(e, dst, src.size() * e->es);
-  if (rc) return rc;
-  if (e->bf16) {
-    std::vector<uint16_t> tmp(src.size());
-    for (size_t i = 0; i < src.size(); ++i) tmp[i] = f32_to_bf16_rne(src[i]);
-    HIP_TRY(hipMemcpy(*dst, tmp.data(), tmp.size() * 2, hipMemcpyHostToDevice));
-  } else {
-    HIP_TRY(hipMemcpy(*dst, src.data(), src.size() * 4, hipMemcpyHostToDevice));
-  }
-  return WF_OK;
-}
 
 // Convolution kernel [c_out, c_in, 3] -> GEMM weight [c_out, kp], column k*c_in + m = W[c, m, k],
 // zero in the padding columns.
@@ -208,73 +123,6 @@ int check_config(const wf_config *c) {
   return WF_OK;
 }
 
-hipEvent_t get_event(wf_encoder *e) {
-  if (!e->evt_pool.empty()) {
-    hipEvent_t ev = e->evt_pool.back();
-    e->evt_pool.pop_back();
-    return ev;
-  }
-  hipEvent_t ev = nullptr;
-  if (hipEventCreate(&ev) != hipSuccess) return nullptr;
-  return ev;
-}
-
-// Brackets one launch with events when profiling is on.
-struct Scope {
-  wf_encoder *e;
-  hipStream_t s;
-  ProfRec rec{};
-  bool on;
-  Scope(wf_encoder *enc, hipStream_t st, int cls, double flops, double bytes) : e(enc), s(st), on(enc->profiling) {
-    if (!on) return;
-    rec.cls = cls; rec.flops = flops; rec.bytes = bytes;
-    rec.t0 = get_event(e); rec.t1 = get_event(e);
-    if (!rec.t0 || !rec.t1) { on = false; return; }
-    (void)hipEventRecord(rec.t0, s);
-  }
-  ~Scope() {
-    if (!on) return;
-    (void)hipEventRecord(rec.t1, s);
-    e->prof.push_back(rec);
-  }
-};
-
-// a_rows x a_cols: the part of the activation operand the launch reads (once, algorithmically).
-int run_gemm(wf_encoder *e, hipStream_t s, int cls, const GemmArgs &a, AMode am, Epilogue ep, int k_real, int out_bytes,
-             double a_rows, double a_cols) {
-  const double flops = 2.0 * a.M * a.N * k_real;
-  double bytes = a_rows * a_cols * e->es + (double)a.N * k_real * e->es + (double)a.M * a.N * out_bytes;
-  if (ep == EPI_BIAS_RESID) bytes += (double)a.M * a.N * 4;
-  Scope sc(e, s, cls, flops, bytes);
-  hipError_t err = e->bf16 ? launch_gemm_bf16(a, am, ep, s) : launch_gemm_f32(a, am, ep, s);
-  if (err != hipSuccess) return fail(WF_E_HIP, "%s launch: %s", kClassNames[cls], hipGetErrorString(err));
-  return WF_OK;
-}
-
-int run_ln(wf_encoder *e, hipStream_t s, int cls, const float *x, const float *g, const float *b, void *out, int out_bf16, int M) {
-  const int d = e->cfg.d_model;
-  Scope sc(e, s, cls, 0.0, (double)M * d * (4 + (out_bf16 ? 2 : 4)));
-  hipError_t err = launch_layernorm(x, g, b, out, out_bf16, M, d, e->cfg.ln_eps, s);
-  if (err != hipSuccess) return fail(WF_E_HIP, "%s launch: %s", kClassNames[cls], hipGetErrorString(err));
-  return WF_OK;
-}
-
-// Attention work list: one item per (stream, block of q_tile queries), longest streams first so the
-// expensive items are scheduled before the cheap ones fill in.
-int build_work(const int32_t *cu_seqlens, int B, int q_tile, int32_t *work) {
-  std::vector<std::pair<int, int>> order(B);
-  for (int i = 0; i < B; ++i) order[i] = {cu_seqlens[i + 1] - cu_seqlens[i], i};
-  std::stable_sort(order.begin(), order.end(), [](const std::pair<int, int> &a, const std::pair<int, int> &b) { return a.first > b.first; });
-  int n = 0;
-  for (const auto &o : order)
-    for (int q0 = 0; q0 < o.first; q0 += q_tile) {
-      work[2 * n] = o.second;
-      work[2 * n + 1] = q0;
-      ++n;
-    }
-  return n;
-}
-
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -301,20 +149,14 @@ int wf_kernel_class_count(void) { return KC_COUNT; }
 
 void wf_encoder_destroy(wf_encoder *e) {
   if (!e) return;
-  (void)hipSetDevice(e->device);
-  (void)hipDeviceSynchronize();
-  for (auto &r : e->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
-  for (auto ev : e->evt_pool) (void)hipEventDestroy(ev);
-  for (int i = 0; i < kStagingSlots; ++i) {
-    if (e->stage_host[i]) (void)hipHostFree(e->stage_host[i]);
-    if (e->stage_evt[i]) (void)hipEventDestroy(e->stage_evt[i]);
-  }
-  for (void *p : e->allocs) (void)hipFree(p);
+  release(e);
   delete e;
 }
 
 static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w) {
   e->cfg = *cfg;
+  e->class_names = kClassNames;
+  e->n_classes = KC_COUNT;
   if (e->cfg.ln_eps <= 0.0f) e->cfg.ln_eps = 1e-5f;
   e->bf16 = cfg->precision == WF_PRECISION_BF16;
   e->es = e->bf16 ? 2 : 4;
@@ -395,10 +237,7 @@ static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w)
   if ((rc = dev_alloc(e, (void **)&e->tok_pos, (size_t)Mx * 4))) return rc;
   e->idx_ints = 4 * ((int64_t)cfg->max_streams + 1) + 2 * e->max_work;
   if ((rc = dev_alloc(e, (void **)&e->idx_dev, (size_t)e->idx_ints * 4))) return rc;
-  for (int i = 0; i < kStagingSlots; ++i) {
-    HIP_TRY(hipHostMalloc((void **)&e->stage_host[i], (size_t)e->idx_ints * 4, hipHostMallocDefault));
-    HIP_TRY(hipEventCreateWithFlags(&e->stage_evt[i], hipEventDisableTiming));
-  }
+  if ((rc = staging_create(e, (size_t)e->idx_ints))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   return WF_OK;
 }
@@ -440,13 +279,14 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
       if (frame_offset[i] < 0) return fail(WF_E_INVALID_ARG, "frame_offset[%d] = %d is negative", i, frame_offset[i]);
 
   // ---- plan on the host, into the next pinned staging slot
-  const int slot = e->stage_next;
-  int32_t *hs = e->stage_host[slot];
-  if (e->stage_used[slot]) HIP_TRY(hipEventSynchronize(e->stage_evt[slot]));   // its previous copy has left the buffer
+  int slot;
+  int32_t *hs;
+  int rc = staging_acquire(e, &slot, &hs);
+  if (rc) return rc;
   const int S1 = c.max_streams + 1;
   int32_t *h_cu_frames = hs, *h_cu_seq = hs + S1, *h_off = hs + 2 * S1, *h_nf = hs + 3 * S1, *h_work = hs + 4 * S1;
   Plan plan;
-  int rc = plan_batch(c, n_frames, B, h_cu_frames, h_cu_seq, &plan);
+  rc = plan_batch(c, n_frames, B, h_cu_frames, h_cu_seq, &plan);
   if (rc) return rc;
   const int M = (int)plan.total_tokens, TF = (int)plan.total_frames;
   if (M > out_capacity_tokens)
@@ -458,10 +298,7 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
 
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t idx_bytes = (size_t)(4 * S1 + 2 * n_work) * 4;
-  HIP_TRY(hipMemcpyAsync(e->idx_dev, hs, idx_bytes, hipMemcpyHostToDevice, s));
-  HIP_TRY(hipEventRecord(e->stage_evt[slot], s));
-  e->stage_used[slot] = true;
-  e->stage_next = (slot + 1) % kStagingSlots;
+  if ((rc = staging_submit(e, slot, e->idx_dev, idx_bytes, s))) return rc;
   const int32_t *d_cu_frames = e->idx_dev, *d_cu_seq = e->idx_dev + S1, *d_off = e->idx_dev + 2 * S1, *d_nf = e->idx_dev + 3 * S1,
                 *d_work = e->idx_dev + 4 * S1;
 
@@ -506,7 +343,7 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
   }
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerDev &w = e->layers[l];
-    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln1_g, w.ln1_b, e->u, act_bf16, M))) return rc;
+    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln1_g, w.ln1_b, e->u, act_bf16, M, d, c.ln_eps))) return rc;
     {
       GemmArgs a{};
       a.A = e->u; a.W = w.wqkv; a.bias = w.bqkv; a.out = e->qkv;
@@ -515,7 +352,8 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     }
     {
       AttnArgs a{};
-      a.qkv = e->qkv; a.out = e->u; a.cu_seqlens = d_cu_seq; a.work = d_work;
+      a.q = e->qkv; a.k = (const char *)e->qkv + (size_t)d * es; a.v = (const char *)e->qkv + (size_t)2 * d * es;
+      a.ldq = a.ldkv = 3 * d; a.out = e->u; a.cu_q = a.cu_kv = d_cu_seq; a.work = d_work;
       a.n_work = n_work; a.n_heads = c.n_heads; a.d_model = d; a.B = B; a.M = M;
       a.scale = 0.125f;
       Scope sc(e, s, KC_ATTN, attn_flops, (double)M * 4 * d * es);
@@ -528,7 +366,7 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
       a.M = M; a.N = d; a.K = d; a.lda = d; a.ldo = d;
       if ((rc = run_gemm(e, s, KC_OUT, a, A_PLAIN, EPI_BIAS_RESID, d, 4, M, d))) return rc;
     }
-    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln2_g, w.ln2_b, e->u, act_bf16, M))) return rc;
+    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln2_g, w.ln2_b, e->u, act_bf16, M, d, c.ln_eps))) return rc;
     {
       GemmArgs a{};
       a.A = e->u; a.W = w.w1; a.bias = w.b1; a.out = e->h;
@@ -543,7 +381,7 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     }
   }
   // ---- a9: final LayerNorm straight into the caller's buffer
-  if ((rc = run_ln(e, s, KC_LNF, e->x, e->lnf_g, e->lnf_b, out_dev, out_dtype == WF_DTYPE_BF16, M))) return rc;
+  if ((rc = run_ln(e, s, KC_LNF, e->x, e->lnf_g, e->lnf_b, out_dev, out_dtype == WF_DTYPE_BF16, M, d, c.ln_eps))) return rc;
   return WF_OK;
 }
 
@@ -555,19 +393,7 @@ int wf_encoder_set_profiling(wf_encoder *e, int32_t enabled) {
 
 int wf_encoder_kernel_stats(wf_encoder *e, wf_kernel_stat *stats, int32_t n_stats) {
   if (!e || !stats) return fail(WF_E_INVALID_ARG, "encoder or stats is NULL");
-  if (n_stats < KC_COUNT) return fail(WF_E_INVALID_ARG, "n_stats = %d, need %d", n_stats, (int)KC_COUNT);
-  for (int i = 0; i < KC_COUNT; ++i) stats[i] = wf_kernel_stat{kClassNames[i], 0, 0.0, 0.0, 0.0};
-  for (auto &r : e->prof) {
-    HIP_TRY(hipEventSynchronize(r.t1));
-    float ms = 0.0f;
-    HIP_TRY(hipEventElapsedTime(&ms, r.t0, r.t1));
-    wf_kernel_stat &st = stats[r.cls];
-    st.launches += 1; st.total_ms += ms; st.flops += r.flops; st.bytes += r.bytes;
-    e->evt_pool.push_back(r.t0);
-    e->evt_pool.push_back(r.t1);
-  }
-  e->prof.clear();
-  return WF_OK;
+  return collect_stats(e, stats, n_stats);
 }
 
 // ---- operator-level entry points -------------------------------------------------------------
@@ -611,7 +437,9 @@ int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const
   hipError_t err = hipMemcpyAsync(d_idx, idx.data(), idx.size() * 4, hipMemcpyHostToDevice, s);
   if (err == hipSuccess) {
     AttnArgs a{};
-    a.qkv = qkv_dev; a.out = out_dev; a.cu_seqlens = d_idx; a.work = d_idx + B + 1;
+    const size_t es = precision == WF_PRECISION_BF16 ? 2 : 4;
+    a.q = qkv_dev; a.k = (const char *)qkv_dev + (size_t)n_heads * 64 * es; a.v = (const char *)qkv_dev + (size_t)2 * n_heads * 64 * es;
+    a.ldq = a.ldkv = 3 * n_heads * 64; a.out = out_dev; a.cu_q = a.cu_kv = d_idx; a.work = d_idx + B + 1;
     a.n_work = n_work; a.n_heads = n_heads; a.d_model = n_heads * 64; a.B = B; a.M = M; a.scale = 0.125f;
     err = precision == WF_PRECISION_BF16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s);
   }

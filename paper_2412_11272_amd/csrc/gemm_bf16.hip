@@ -414,7 +414,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       if (m < p.M) *(u32x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nw0 + c * 8) = v;
     }
   } else {
-    // fp32 residual update in place, PW features (PW * 4 bytes per row) per pass
+    // fp32 output: residual update in place (EPI_BIAS_RESID) or plain store (EPI_BIAS_F32), PW features
+    // (PW * 4 bytes per row) per pass
     constexpr int PW = TN >= 64 ? 64 : TN;         // features per pass
     constexpr int RB = PW * 4, CPR = RB / 16, RPI = 64 / CPR;
 #pragma unroll
@@ -446,10 +447,14 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
         const int m = mw0 + r;
         if (m < p.M) {
           f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
-          f32x4 x = *o;
+          if (EPI == EPI_BIAS_RESID) {
+            f32x4 x = *o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) x[e] += v[e];
-          *o = x;
+            for (int e = 0; e < 4; ++e) x[e] += v[e];
+            *o = x;
+          } else {
+            *o = v;
+          }
         }
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);          // reads done before the next pass overwrites the slice
@@ -524,6 +529,8 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU>(a, s);
       case EPI_BIAS_RESID:
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_RESID>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_RESID>(a, s);
+      case EPI_BIAS_F32:
+        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_F32>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_F32>(a, s);
       default: return hipErrorInvalidValue;
     }
   }

@@ -23,6 +23,7 @@ enum Epilogue : int {
   EPI_BIAS_GELU = 1,       // out = GELU(acc + bias)                    (fc1, first convolution)
   EPI_BIAS_RESID = 2,      // out(fp32) += acc + bias, in place         (out-projection, fc2)
   EPI_BIAS_GELU_POS = 3,   // out(fp32) = GELU(acc + bias) + pos[row_pos[r]]   (second convolution)
+  EPI_BIAS_F32 = 4,        // out(fp32) = acc + bias                    (logits)
 };
 
 struct GemmArgs {
@@ -44,11 +45,17 @@ struct GemmArgs {
 };
 
 struct AttnArgs {
-  const void *qkv;          // [M, 3*d]: q | k | v, head h owns columns [64h, 64h+64) of each third
-  void *out;                // [M, d]
-  const int32_t *cu_seqlens;// [B+1]
+  // Head h owns columns [64h, 64h+64) counted from each of the three base pointers.  Queries of stream i
+  // are rows [cu_q[i], cu_q[i+1]) of q (row stride ldq elements), its keys/values rows
+  // [cu_kv[i], cu_kv[i+1]) of k and v (row stride ldkv).  Encoder self-attention: one [M, 3d] matrix
+  // q | k | v and cu_q == cu_kv.  causal != 0 (needs cu_q == cu_kv): query r sees keys 0..r of its stream.
+  const void *q, *k, *v;
+  void *out;                // [Mq, d_model]
+  int32_t ldq, ldkv;
+  const int32_t *cu_q, *cu_kv;   // [B+1] each
   const int32_t *work;      // [n_work][2]: (stream, first query row inside the stream), longest first
-  int32_t n_work, n_heads, d_model, B, M;
+  int32_t n_work, n_heads, d_model, B, M;   // M = total query rows
+  int32_t causal;
   float scale;              // 1/sqrt(64)
 };
 
@@ -68,6 +75,11 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 hipError_t launch_layernorm(const float *x, const float *g, const float *b, void *out, int out_bf16,
                             int32_t M, int32_t d, float eps, hipStream_t s);
 hipError_t launch_prep(const PrepArgs &a, int packed_bf16, hipStream_t s);
+// x[r, :] = table[tok[r], :] + pos[pos_idx[r], :]  (fp32 out; table bf16 or fp32, pos fp32)
+hipError_t launch_embed(const void *table, int table_bf16, const float *pos, const int32_t *tok, const int32_t *pos_idx,
+                        float *x, int32_t rows, int32_t d, hipStream_t s);
+// dst[i, :] = src[row[i], :] for rows of row_bytes bytes (multiple of 16)
+hipError_t launch_gather_rows(const void *src, const int32_t *row, void *dst, int32_t n, int32_t row_bytes, hipStream_t s);
 int attention_q_tile();     // query rows per attention work item
 
 // fp32 debug path ------------------------------------------------------------------------------

@@ -107,7 +107,55 @@ __global__ void __launch_bounds__(256) layernorm_kernel(const float *__restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decoder input: x[r, :] = table[tok[r], :] + pos[pos_idx[r], :], one thread per 4 features.
+template <typename TTAB>
+__global__ void __launch_bounds__(256) embed_kernel(const TTAB *__restrict__ table, const float *__restrict__ pos,
+                                                    const int32_t *__restrict__ tok, const int32_t *__restrict__ pos_idx,
+                                                    float *__restrict__ x, int rows, int d) {
+  const int cpr = d >> 2;
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)rows * cpr) return;
+  const int r = (int)(gid / cpr), c = (int)(gid % cpr) * 4;
+  const TTAB *t = table + (size_t)tok[r] * d + c;
+  const f32x4 pe = *(const f32x4 *)(pos + (size_t)pos_idx[r] * d + c);
+  f32x4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = (float)t[e] + pe[e];
+  *(f32x4 *)(x + (size_t)r * d + c) = v;
+}
+
+// dst[i, :] = src[row[i], :], 16 bytes per thread.
+__global__ void __launch_bounds__(256) gather_rows_kernel(const unsigned char *__restrict__ src, const int32_t *__restrict__ row,
+                                                          unsigned char *__restrict__ dst, int n, int row_bytes) {
+  const int cpr = row_bytes >> 4;
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)n * cpr) return;
+  const int i = (int)(gid / cpr), c = (int)(gid % cpr);
+  *(f32x4 *)(dst + (size_t)i * row_bytes + c * 16) = *(const f32x4 *)(src + (size_t)row[i] * row_bytes + c * 16);
+}
+
 }  // namespace
+
+hipError_t launch_embed(const void *table, int table_bf16, const float *pos, const int32_t *tok, const int32_t *pos_idx,
+                        float *x, int32_t rows, int32_t d, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (d % 4 != 0) return hipErrorInvalidValue;
+  const long n = (long)rows * (d / 4);
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (table_bf16) hipLaunchKernelGGL(embed_kernel<__bf16>, grid, block, 0, s, (const __bf16 *)table, pos, tok, pos_idx, x, rows, d);
+  else hipLaunchKernelGGL(embed_kernel<float>, grid, block, 0, s, (const float *)table, pos, tok, pos_idx, x, rows, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void *src, const int32_t *row, void *dst, int32_t n, int32_t row_bytes, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  if (row_bytes % 16 != 0) return hipErrorInvalidValue;
+  const long t = (long)n * (row_bytes / 16);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((t + 255) / 256)), dim3(256), 0, s, (const unsigned char *)src, row,
+                     (unsigned char *)dst, n, row_bytes);
+  return hipGetLastError();
+}
 
 hipError_t launch_layernorm(const float *x, const float *g, const float *b, void *out, int out_bf16,
                             int32_t M, int32_t d, float eps, hipStream_t s) {
