@@ -79,6 +79,7 @@ def bench_frontend(wl, n_frames, steps, warmup):
     out = torch.empty((frames, wl.shape.n_mels), device="cuda", dtype=torch.float32)
     for _ in range(warmup):
         fe.logmel(audio, offs, lens, out=out)
+    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
@@ -114,6 +115,7 @@ def bench_prefill(wl, states, cu, steps, warmup):
     def timed(fn):
         for _ in range(warmup):
             fn()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(steps):

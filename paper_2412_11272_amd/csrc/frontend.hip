@@ -187,6 +187,11 @@ __global__ void __launch_bounds__(256) normalize_kernel(FeArgs p) {
 
 }  // namespace
 
+// Pinned staging slots for the per-call index arrays.  A slot is reused only after its copy has left it; the
+// ring is deep enough that a caller who enqueues short calls back to back blocks on work issued many calls
+// ago (waking from such a wait costs more than several of these calls take on the GPU).
+constexpr int kIdxSlots = 32;
+
 struct wf_frontend {
   wf_frontend_config cfg{};
   int64_t max_frames = 0;
@@ -194,9 +199,9 @@ struct wf_frontend {
   float *hush = nullptr, *window = nullptr, *basis_c = nullptr, *basis_s = nullptr, *fbank = nullptr, *V = nullptr;
   int32_t *fb_lo = nullptr, *fb_hi = nullptr, *frame_stream = nullptr, *frame_t = nullptr, *smax = nullptr;
   unsigned char *idx_dev = nullptr;      // [B] int64 offsets | [B] int32 n_samples | [B+1] int32 cu_frames
-  unsigned char *idx_host[4] = {};
-  hipEvent_t idx_evt[4] = {};
-  bool idx_used[4] = {};
+  unsigned char *idx_host[kIdxSlots] = {};
+  hipEvent_t idx_evt[kIdxSlots] = {};
+  bool idx_used[kIdxSlots] = {};
   int idx_next = 0;
   size_t idx_bytes = 0;
 };
@@ -274,7 +279,7 @@ int fe_create(wf_frontend *fe, const wf_frontend_config *cfg, const float *hush_
   fe->idx_bytes = (size_t)cfg->max_streams * 8 + (size_t)cfg->max_streams * 4 + (size_t)(cfg->max_streams + 1) * 4;
   fe->idx_bytes = (fe->idx_bytes + 15) / 16 * 16;
   if ((rc = fe_alloc(fe, (void **)&fe->idx_dev, fe->idx_bytes))) return rc;
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < kIdxSlots; ++i) {
     FE_HIP_TRY(hipHostMalloc((void **)&fe->idx_host[i], fe->idx_bytes, hipHostMallocDefault));
     FE_HIP_TRY(hipEventCreateWithFlags(&fe->idx_evt[i], hipEventDisableTiming));
   }
@@ -291,7 +296,7 @@ extern "C" {
 void wf_frontend_destroy(wf_frontend *fe) {
   if (!fe) return;
   (void)hipDeviceSynchronize();
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < kIdxSlots; ++i) {
     if (fe->idx_host[i]) (void)hipHostFree(fe->idx_host[i]);
     if (fe->idx_evt[i]) (void)hipEventDestroy(fe->idx_evt[i]);
   }
@@ -359,7 +364,7 @@ int wf_logmel_batch(wf_frontend *fe, const float *audio_dev, const int64_t *samp
   FE_HIP_TRY(hipMemcpyAsync(fe->idx_dev, hs, fe->idx_bytes, hipMemcpyHostToDevice, s));
   FE_HIP_TRY(hipEventRecord(fe->idx_evt[slot], s));
   fe->idx_used[slot] = true;
-  fe->idx_next = (slot + 1) % 4;
+  fe->idx_next = (slot + 1) % kIdxSlots;
   if (frames == 0) return WF_OK;
 
   FeArgs a{};

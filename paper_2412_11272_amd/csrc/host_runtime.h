@@ -48,7 +48,9 @@ inline uint16_t f32_to_bf16_rne(float f) {
 
 struct ProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
-constexpr int kStagingSlots = 4;
+// Deep enough that a caller enqueueing short calls back to back only ever blocks on a copy issued many
+// calls ago (waking from such a wait costs more than several short calls take on the GPU).
+constexpr int kStagingSlots = 32;
 
 // What every runtime object owns on the device and the host.
 struct DevCtx {
