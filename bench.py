@@ -144,6 +144,49 @@ def bench_prefill(wl, states, cu, steps, warmup):
             "prefill_ms": round(ms_pf, 3), "prefill_tflops": round(fl_pf / ms_pf / 1e9, 1), "dtype": "bf16", "kernels": kern}
 
 
+def bench_rounds(wl, weights, hush, n_rounds):
+    """Processing rounds over the workload's streams (Section "Operations"; step length and best effort,
+    Section "Key Implementation Details"): every stream ingests audio in real time, each round encodes the
+    current buffers as one ragged batch; virtual time advances by the measured round time.  Reported per
+    step length, with the padded-30 s-window baseline next to it (not part of `value`)."""
+    import numpy as np
+    import torch
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+    S, H, MAXF, TRACK = len(wl.n_frames), wl.hush_frames, 3000, 6016
+    rng = np.random.default_rng(wl.seeds["lengths"] + 100)
+    starts = [int(x) for x in rng.integers(0, 15_000_000, size=S)]        # streams out of phase by up to 15 s
+    tracks = torch.from_numpy(np.clip(rng.normal(-0.3, 0.4, size=(S, TRACK, wl.shape.n_mels)), -1, 1).astype(np.float32)).cuda().bfloat16()
+    out = torch.empty((S * (MAXF + H + 1) // 2, wl.shape.d_model), device="cuda", dtype=torch.bfloat16)
+    res = []
+    for mode in ("ragged+hush", "padded-30s"):
+        pad = 0 if mode == "ragged+hush" else MAXF
+        hf = H if pad == 0 else 0
+        cfg = wf.make_config(wl.shape, hf, S, S * (MAXF + hf), MAXF + hf, wf.WF_PRECISION_BF16)
+        enc = wf.Encoder(cfg, weights, hush if hf else None)
+        for step_s in (0.01, 0.5, 1.0, 2.0):
+            sim = wf.Rounds(starts, int(step_s * 1e6), 1500, 100, MAXF)
+            while True:                                   # host-only fast-forward to t = 20 s: buffers in steady state
+                s, _, _ = sim.begin()
+                sim.end(1000)
+                if s >= 20_000_000:
+                    break
+            sim.run(enc, tracks, 2, out, pad_to_frames=pad)
+            sim.reset_stats()
+            rec = sim.run(enc, tracks, n_rounds, out, pad_to_frames=pad)
+            st = sim.stats()
+            sim.close()
+            span = (rec[-1]["end_us"] - rec[0]["start_us"]) / 1e6
+            res.append({"mode": mode, "step_s": step_s, "rounds": n_rounds,
+                        "round_ms_mean": round(st["mean_proc_us"] / 1e3, 2), "round_ms_max": round(st["max_proc_us"] / 1e3, 2),
+                        "tokens_per_round": round(sum(r["tokens"] for r in rec) / n_rounds, 1),
+                        "streams_per_round": round(sum(r["n_active"] for r in rec) / n_rounds, 1),
+                        "word_latency_s": round(st["mean_latency_us"] / 1e6, 4),
+                        "gpu_busy_frac": round(sum(r["proc_us"] for r in rec) / 1e6 / span, 4)})
+        enc.close()
+    return {"streams": S, "buffer_trim_s": 15.0, "runs": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,6 +198,8 @@ def main():
                     help="also time the raw-audio log-mel front end on audio of the same lengths (reported separately)")
     ap.add_argument("--prefill", action="store_true",
                     help="also time the decoder-side steps on the encoder states of the same batch (reported separately)")
+    ap.add_argument("--rounds", type=int, default=0,
+                    help="also run this many processing rounds per step length through the round driver (reported separately)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -258,6 +303,9 @@ def main():
     if args.prefill:
         result["prefill"] = bench_prefill(wl, out, cu, args.steps, args.warmup)
     del mel, out
+    if args.rounds > 0:
+        torch.cuda.empty_cache()
+        result["rounds"] = bench_rounds(wl, weights, hush, args.rounds)
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, weights, hush, mels)

@@ -158,6 +158,8 @@ typedef struct {
 int wf_kernel_class_count(void);
 int wf_encoder_set_profiling(wf_encoder *enc, int32_t enabled);
 int wf_encoder_kernel_stats(wf_encoder *enc, wf_kernel_stat *stats, int32_t n_stats);
+/* The configuration the encoder was created with (ln_eps as resolved). */
+int wf_encoder_get_config(const wf_encoder *enc, wf_config *cfg);
 
 /*
  * Operator-level entry points: single steps of the encoder on caller-provided DEVICE buffers, for
@@ -283,6 +285,64 @@ void wf_decoder_destroy(wf_decoder *dec);          /* NULL-safe */
 int wf_decoder_kernel_class_count(void);
 int wf_decoder_set_profiling(wf_decoder *dec, int32_t enabled);
 int wf_decoder_kernel_stats(wf_decoder *dec, wf_kernel_stat *stats, int32_t n_stats);
+
+/* ---- Processing rounds over many concurrent streams ---------------------------------------------------
+ * Host-side bookkeeping of the paper's online operation (Section "Operations": each round snapshots the
+ * audio buffers; output is materialized once two consecutive rounds agree (LocalAgreement-2); buffers are
+ * trimmed of materialized audio; a word's latency = wait until the next round + at least two rounds.
+ * Section "Key Implementation Details": step length; below a round's processing time the rounds run back
+ * to back, "best effort"), and a driver that runs such rounds through an encoder, one ragged batch per
+ * round.  Integers throughout: times in microseconds, buffers in 10 ms frames.
+ *
+ * Rules.  Stream i ingests audio continuously from start_us[i].  Round k starts at s_0 = min(start_us) +
+ * step_us, s_{k+1} = max(s_k + step_us, e_k), and ends at e_k = s_k + proc_k.  Its snapshot of stream i
+ * holds n_i = floor((s_k - buffer start) / 10 ms) frames (0 before the stream starts; a buffer longer than
+ * max_frames loses its oldest frames).  After round k, a buffer that held >= trim_frames frames drops the
+ * frames that arrived before s_{k-1} (seen by two consecutive rounds, i.e. materialized) except
+ * keep_frames of them.  Audio that arrived in (s_{k-1}, s_k] is first seen by round k and materialized at
+ * e_{k+1}; mean_latency_us averages (materialization time - arrival time) over all such audio.
+ *
+ * wf_rounds_begin  opens the next round: *round_start_us = s_k, n_frames / first_frame: HOST [n_streams]
+ *                  (first_frame = index, in the stream's own frame count since start_us[i], of the buffer's
+ *                  first frame).  WF_E_INVALID_ARG if a round is already open.
+ * wf_rounds_end    closes it with its processing time; *round_end_us (may be NULL) = e_k.
+ * wf_run_rounds    runs n_rounds rounds: each round's active streams (n_i >= 1) are encoded as one ragged
+ *                  batch by wf_encode_batch on hip_stream, the round's processing time is the wall-clock
+ *                  time from planning to completion, and the virtual clock advances by it.  tracks_dev:
+ *                  DEVICE [n_streams, track_frames, n_mels] (mel_dtype) synthetic per-stream feature tracks,
+ *                  read circularly (track_frames > max_frames); pad_to_frames > 0 replaces every active
+ *                  stream's length by pad_to_frames (the padded-window baseline; use an encoder without
+ *                  hush).  out_dev receives the last round's states; records: HOST [n_rounds].
+ */
+typedef struct wf_rounds wf_rounds;
+typedef struct {
+  int32_t n_streams;
+  int64_t step_us;              /* >= 1 */
+  int32_t trim_frames;          /* 1 .. max_frames */
+  int32_t keep_frames;          /* >= 0 */
+  int32_t max_frames;           /* the model's window, 3000 = 30 s */
+} wf_rounds_config;
+typedef struct {
+  int64_t rounds;
+  double mean_latency_us, mean_proc_us;
+  int64_t max_proc_us, frames_total, last_round_end_us;
+} wf_rounds_stats;
+typedef struct {
+  int64_t start_us, end_us, proc_us;
+  int64_t frames;               /* frames encoded this round (hush / padding included) */
+  int64_t tokens;
+  int32_t n_active, reserved;
+} wf_round_record;
+
+int wf_rounds_create(const wf_rounds_config *cfg, const int64_t *start_us, wf_rounds **out);
+int wf_rounds_begin(wf_rounds *r, int64_t *round_start_us, int32_t *n_frames, int32_t *first_frame);
+int wf_rounds_end(wf_rounds *r, int64_t proc_us, int64_t *round_end_us);
+int wf_rounds_get_stats(const wf_rounds *r, wf_rounds_stats *stats);
+int wf_rounds_reset_stats(wf_rounds *r);         /* statistics restart from here (e.g. after a warm-up); state is kept */
+void wf_rounds_destroy(wf_rounds *r);            /* NULL-safe */
+int wf_run_rounds(wf_rounds *r, wf_encoder *enc, const void *tracks_dev, int32_t mel_dtype, int64_t track_frames,
+                  int32_t pad_to_frames, int32_t n_rounds, void *out_dev, int32_t out_dtype, int64_t out_capacity_tokens,
+                  wf_round_record *records, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -68,6 +68,21 @@ class WfDecoderWeights(C.Structure):
     _fields_ = [("tok_emb", _fp), ("pos_emb", _fp), ("layers", C.POINTER(WfDecoderLayerWeights)), ("lnf_g", _fp), ("lnf_b", _fp)]
 
 
+class WfRoundsConfig(C.Structure):
+    _fields_ = [("n_streams", C.c_int32), ("step_us", C.c_int64), ("trim_frames", C.c_int32), ("keep_frames", C.c_int32),
+                ("max_frames", C.c_int32)]
+
+
+class WfRoundsStats(C.Structure):
+    _fields_ = [("rounds", C.c_int64), ("mean_latency_us", C.c_double), ("mean_proc_us", C.c_double),
+                ("max_proc_us", C.c_int64), ("frames_total", C.c_int64), ("last_round_end_us", C.c_int64)]
+
+
+class WfRoundRecord(C.Structure):
+    _fields_ = [("start_us", C.c_int64), ("end_us", C.c_int64), ("proc_us", C.c_int64), ("frames", C.c_int64),
+                ("tokens", C.c_int64), ("n_active", C.c_int32), ("reserved", C.c_int32)]
+
+
 class WfError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"wf error {code}: {msg}")
@@ -81,7 +96,9 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_op_linear", "wf_op_layernorm", "wf_op_attention",
            "wf_frontend_create", "wf_logmel_batch", "wf_frontend_destroy",
            "wf_decoder_config_check", "wf_decoder_create", "wf_cross_kv", "wf_prefill", "wf_decoder_destroy",
-           "wf_decoder_kernel_class_count", "wf_decoder_set_profiling", "wf_decoder_kernel_stats"]
+           "wf_decoder_kernel_class_count", "wf_decoder_set_profiling", "wf_decoder_kernel_stats",
+           "wf_encoder_get_config", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
+           "wf_rounds_destroy", "wf_run_rounds"]
 
 
 def lib() -> C.CDLL:
@@ -124,6 +141,17 @@ def lib() -> C.CDLL:
     L.wf_decoder_destroy.restype = None
     L.wf_decoder_set_profiling.argtypes = [C.c_void_p, C.c_int32]
     L.wf_decoder_kernel_stats.argtypes = [C.c_void_p, C.POINTER(WfKernelStat), C.c_int32]
+    L.wf_encoder_get_config.argtypes = [C.c_void_p, C.POINTER(WfConfig)]
+    _lp = C.POINTER(C.c_int64)
+    L.wf_rounds_create.argtypes = [C.POINTER(WfRoundsConfig), _lp, C.POINTER(C.c_void_p)]
+    L.wf_rounds_begin.argtypes = [C.c_void_p, _lp, _ip, _ip]
+    L.wf_rounds_end.argtypes = [C.c_void_p, C.c_int64, _lp]
+    L.wf_rounds_get_stats.argtypes = [C.c_void_p, C.POINTER(WfRoundsStats)]
+    L.wf_rounds_reset_stats.argtypes = [C.c_void_p]
+    L.wf_rounds_destroy.argtypes = [C.c_void_p]
+    L.wf_rounds_destroy.restype = None
+    L.wf_run_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                                C.c_int32, C.c_int64, C.POINTER(WfRoundRecord), C.c_void_p]
     _lib = L
     return L
 
@@ -351,6 +379,58 @@ class Decoder:
     def close(self):
         if self._h:
             lib().wf_decoder_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Rounds:
+    """Owns one wf_rounds: snapshot / trimming / latency bookkeeping of processing rounds (host only),
+    and run(): the driver that pushes every round's ragged batch through an Encoder."""
+
+    def __init__(self, start_us: Sequence[int], step_us: int, trim_frames: int = 1500, keep_frames: int = 100,
+                 max_frames: int = 3000):
+        st = np.ascontiguousarray(start_us, dtype=np.int64)
+        self.cfg = WfRoundsConfig(len(st), step_us, trim_frames, keep_frames, max_frames)
+        self._h = C.c_void_p(None)
+        _check(lib().wf_rounds_create(C.byref(self.cfg), st.ctypes.data_as(C.POINTER(C.c_int64)), C.byref(self._h)))
+
+    def begin(self):
+        S = self.cfg.n_streams
+        n, f, s = np.zeros(S, np.int32), np.zeros(S, np.int32), C.c_int64(0)
+        _check(lib().wf_rounds_begin(self._h, C.byref(s), n.ctypes.data_as(_ip), f.ctypes.data_as(_ip)))
+        return s.value, n, f
+
+    def end(self, proc_us: int) -> int:
+        e = C.c_int64(0)
+        _check(lib().wf_rounds_end(self._h, int(proc_us), C.byref(e)))
+        return e.value
+
+    def stats(self) -> dict:
+        st = WfRoundsStats()
+        _check(lib().wf_rounds_get_stats(self._h, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in WfRoundsStats._fields_}
+
+    def reset_stats(self):
+        _check(lib().wf_rounds_reset_stats(self._h))
+
+    def run(self, enc: "Encoder", tracks, n_rounds: int, out, pad_to_frames: int = 0, stream=None) -> List[dict]:
+        """tracks: CUDA [n_streams, track_frames, n_mels]; out: CUDA [capacity, d_model].  Returns per-round records."""
+        import torch
+        rec = (WfRoundRecord * max(n_rounds, 1))()
+        s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        _check(lib().wf_run_rounds(self._h, enc._h, C.c_void_p(tracks.data_ptr()), _torch_dtype_code(tracks.dtype), tracks.shape[1],
+                                   pad_to_frames, n_rounds, C.c_void_p(out.data_ptr()), _torch_dtype_code(out.dtype), out.shape[0],
+                                   rec, C.c_void_p(s)))
+        return [{k: getattr(rec[i], k) for k, _ in WfRoundRecord._fields_ if k != "reserved"} for i in range(n_rounds)]
+
+    def close(self):
+        if self._h:
+            lib().wf_rounds_destroy(self._h)
             self._h = C.c_void_p(None)
 
     def __del__(self):

@@ -385,6 +385,12 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
   return WF_OK;
 }
 
+int wf_encoder_get_config(const wf_encoder *e, wf_config *cfg) {
+  if (!e || !cfg) return fail(WF_E_INVALID_ARG, "encoder or cfg is NULL");
+  *cfg = e->cfg;
+  return WF_OK;
+}
+
 int wf_encoder_set_profiling(wf_encoder *e, int32_t enabled) {
   if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
   e->profiling = enabled != 0;
