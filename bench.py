@@ -187,6 +187,27 @@ def bench_rounds(wl, weights, hush, n_rounds):
     return {"streams": S, "buffer_trim_s": 15.0, "runs": res}
 
 
+def bench_beam(n_sessions):
+    """Beam-pruning state machine on synthetic decoding sessions (host only; reported separately)."""
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+    sessions = synth.make_beam_sessions(n_sessions, synth.BASE_SEED + 90)
+    bp = wf.BeamPruner(synth.BEAM_SIZE, [], synth.TEXT_VOCAB, synth.PUNCT_IDS)
+    steps = reduced = beam_sum = 0
+    t0 = time.perf_counter()
+    for ref, cur in sessions:
+        bp.reset(ref)
+        beams, _ = bp.session(cur)
+        steps += len(beams)
+        reduced += int((beams < synth.BEAM_SIZE).sum())
+        beam_sum += int(beams.sum())
+    dt = time.perf_counter() - t0
+    bp.close()
+    return {"sessions": n_sessions, "decoding_steps": steps, "reduce_ratio": round(reduced / steps, 4),
+            "avg_beam": round(beam_sum / steps, 3), "original_beam": synth.BEAM_SIZE,
+            "steps_per_s_one_core_incl_binding": round(steps / dt, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +221,8 @@ def main():
                     help="also time the decoder-side steps on the encoder states of the same batch (reported separately)")
     ap.add_argument("--rounds", type=int, default=0,
                     help="also run this many processing rounds per step length through the round driver (reported separately)")
+    ap.add_argument("--beam-sessions", type=int, default=0,
+                    help="also run the beam-pruning state machine over this many synthetic decoding sessions (host only)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -303,6 +326,8 @@ def main():
     if args.prefill:
         result["prefill"] = bench_prefill(wl, out, cu, args.steps, args.warmup)
     del mel, out
+    if args.beam_sessions > 0:
+        result["beam_pruning"] = bench_beam(args.beam_sessions)
     if args.rounds > 0:
         torch.cuda.empty_cache()
         result["rounds"] = bench_rounds(wl, weights, hush, args.rounds)

@@ -344,6 +344,37 @@ int wf_run_rounds(wf_rounds *r, wf_encoder *enc, const void *tracks_dev, int32_t
                   int32_t pad_to_frames, int32_t n_rounds, void *out_dev, int32_t out_dtype, int64_t out_capacity_tokens,
                   wf_round_record *records, void *hip_stream);
 
+/* ---- Beam pruning ------------------------------------------------------------------------------------
+ * The reference-based beam-size state machine of the paper's Section "Beam pruning" (search-based
+ * reference alignment, selective transcript token matching and beam reduction, fallback mechanism).  Host
+ * integer logic, no GPU call.  The reference is the token list of the previous processing round; each
+ * wf_beam_pruner_step receives the highest-probability token of one decoding step of the current round.
+ *   - the beam size starts at 1;
+ *   - a punctuation token (listed in punct_ids) or a timestamp / special token (id >= special_from) is
+ *     skipped: beam and reference index stay as they are; such tokens are also left out of the reference;
+ *   - the first ordinary token is searched in the reference; its first occurrence i aligns the session
+ *     (the next ordinary token is compared with reference token i + 1), no occurrence falls back;
+ *   - afterwards an ordinary token equal to the reference token at the index keeps the beam at 1 and
+ *     advances the index; a different one, or one arriving after the reference is used up, falls back;
+ *   - a fallback restores the original beam size for the rest of the session.
+ * Events: 0 skipped, 1 aligned, 2 matched, 3 fallback (alignment failed), 4 fallback (mismatch),
+ * 5 fallback (reference used up), 6 already at the original beam size.
+ *
+ * wf_beam_pruner_create   ref_tokens HOST [n_ref] (n_ref >= 0, copied), punct_ids HOST [n_punct] (copied).
+ * wf_beam_pruner_step     *event and *next_beam (either may be NULL): the event of this step and the beam
+ *                         size the NEXT decoding step should run with.
+ * wf_beam_pruner_reset    new decoding session against a new reference (same beam size and token classes).
+ * wf_beam_prune_session   one whole session: best_tokens HOST [n]; beam_for_step / events HOST [n] (either may
+ *                         be NULL): the beam size each step ran with and its event.
+ */
+typedef struct wf_beam_pruner wf_beam_pruner;
+int wf_beam_pruner_create(int32_t beam_size, const int32_t *ref_tokens, int32_t n_ref, int32_t special_from,
+                          const int32_t *punct_ids, int32_t n_punct, wf_beam_pruner **out);
+int wf_beam_pruner_step(wf_beam_pruner *p, int32_t best_token, int32_t *event, int32_t *next_beam);
+int wf_beam_pruner_reset(wf_beam_pruner *p, const int32_t *ref_tokens, int32_t n_ref);
+int wf_beam_prune_session(wf_beam_pruner *p, const int32_t *best_tokens, int32_t n, int32_t *beam_for_step, int32_t *events);
+void wf_beam_pruner_destroy(wf_beam_pruner *p);  /* NULL-safe */
+
 #ifdef __cplusplus
 }
 #endif

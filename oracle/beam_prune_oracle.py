@@ -12,7 +12,10 @@ step of the current round and receives that step's highest-probability token.
   3. Matching (later steps): the best token is compared with the reference token at the index.  Equal:
      beam stays 1, the index advances by one.  Different: fallback.
   4. Selectivity: if the best token is a punctuation, timestamp or any other special token, the step is
-     skipped: beam stays 1, the index does not move (this also holds before alignment).
+     skipped: beam stays 1, the index does not move (this also holds before alignment).  The same kinds
+     of token are left out of the reference list: the paper's stated purpose of the rule is that
+     misplaced timestamps and punctuation must not disturb the matching, which they would if an ordinary
+     token could meet a punctuation token on the reference side.
   5. Fallback: the beam returns to the original size.
 
 Readings where the paper is silent: alignment waits for the first ordinary token (Whisper-style outputs
@@ -39,9 +42,9 @@ class BeamPruner:
     def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Iterable[int] = ()):
         assert beam_size >= 1
         self.full = int(beam_size)
-        self.ref = [int(t) for t in reference]
         self.special_from = int(special_from)
         self.punct = set(int(t) for t in punctuation)
+        self.ref = [int(t) for t in reference if not self.is_exempt(int(t))]
         self.beam = 1
         self.idx = None            # reference index; None until aligned
         self.fallen = False

@@ -98,7 +98,9 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_decoder_config_check", "wf_decoder_create", "wf_cross_kv", "wf_prefill", "wf_decoder_destroy",
            "wf_decoder_kernel_class_count", "wf_decoder_set_profiling", "wf_decoder_kernel_stats",
            "wf_encoder_get_config", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
-           "wf_rounds_destroy", "wf_run_rounds"]
+           "wf_rounds_destroy", "wf_run_rounds",
+           "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
+           "wf_beam_pruner_destroy"]
 
 
 def lib() -> C.CDLL:
@@ -148,6 +150,12 @@ def lib() -> C.CDLL:
     L.wf_rounds_end.argtypes = [C.c_void_p, C.c_int64, _lp]
     L.wf_rounds_get_stats.argtypes = [C.c_void_p, C.POINTER(WfRoundsStats)]
     L.wf_rounds_reset_stats.argtypes = [C.c_void_p]
+    L.wf_beam_pruner_create.argtypes = [C.c_int32, _ip, C.c_int32, C.c_int32, _ip, C.c_int32, C.POINTER(C.c_void_p)]
+    L.wf_beam_pruner_step.argtypes = [C.c_void_p, C.c_int32, _ip, _ip]
+    L.wf_beam_pruner_reset.argtypes = [C.c_void_p, _ip, C.c_int32]
+    L.wf_beam_prune_session.argtypes = [C.c_void_p, _ip, C.c_int32, _ip, _ip]
+    L.wf_beam_pruner_destroy.argtypes = [C.c_void_p]
+    L.wf_beam_pruner_destroy.restype = None
     L.wf_rounds_destroy.argtypes = [C.c_void_p]
     L.wf_rounds_destroy.restype = None
     L.wf_run_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
@@ -431,6 +439,45 @@ class Rounds:
     def close(self):
         if self._h:
             lib().wf_rounds_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class BeamPruner:
+    """Owns one wf_beam_pruner: the reference-based beam-size state machine (host only)."""
+
+    def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Sequence[int] = ()):
+        ref = np.ascontiguousarray(reference, dtype=np.int32)
+        pun = np.ascontiguousarray(list(punctuation), dtype=np.int32)
+        self._h = C.c_void_p(None)
+        _check(lib().wf_beam_pruner_create(beam_size, ref.ctypes.data_as(_ip) if len(ref) else None, len(ref), special_from,
+                                           pun.ctypes.data_as(_ip) if len(pun) else None, len(pun), C.byref(self._h)))
+
+    def step(self, best_token: int) -> Tuple[int, int]:
+        ev, nb = C.c_int32(0), C.c_int32(0)
+        _check(lib().wf_beam_pruner_step(self._h, int(best_token), C.byref(ev), C.byref(nb)))
+        return ev.value, nb.value
+
+    def reset(self, reference: Sequence[int]):
+        ref = np.ascontiguousarray(reference, dtype=np.int32)
+        _check(lib().wf_beam_pruner_reset(self._h, ref.ctypes.data_as(_ip) if len(ref) else None, len(ref)))
+
+    def session(self, best_tokens: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+        """Returns (beam size each step ran with, event of each step)."""
+        tok = np.ascontiguousarray(best_tokens, dtype=np.int32)
+        beams, events = np.zeros(len(tok), np.int32), np.zeros(len(tok), np.int32)
+        _check(lib().wf_beam_prune_session(self._h, tok.ctypes.data_as(_ip) if len(tok) else None, len(tok),
+                                           beams.ctypes.data_as(_ip), events.ctypes.data_as(_ip)))
+        return beams, events
+
+    def close(self):
+        if self._h:
+            lib().wf_beam_pruner_destroy(self._h)
             self._h = C.c_void_p(None)
 
     def __del__(self):

@@ -247,6 +247,41 @@ def make_enc_states(n_tokens: int, d_model: int, seed: int) -> np.ndarray:
     return rng.standard_normal((n_tokens, d_model)).astype(np.float32)
 
 
+# ---- beam pruning: synthetic decoding sessions ------------------------------------------------------
+
+BEAM_SIZE = 5                 # Section "CPU/GPU pipelining", categorization of workloads: 5 hypotheses per round
+SESSION_TOKENS = 150          # same passage: a decoding session averages 150 rounds
+TEXT_VOCAB = 50257            # ids below this are ordinary text tokens; timestamps / special tokens lie above
+PUNCT_IDS = (11, 13, 30, 0)   # a handful of ids standing in for punctuation tokens
+
+
+def make_beam_sessions(n_sessions: int, seed: int, n_tokens: int = SESSION_TOKENS, trim_max: int = 40, new_max: int = 25,
+                       p_substitute: float = 0.004, p_punct: float = 0.08, p_timestamp: float = 0.06):
+    """(reference, best_tokens) pairs shaped like consecutive processing rounds over a sliding buffer: the new
+    transcript starts somewhere inside the previous one (front trimmed), repeats it with rare substitutions,
+    inconsistent punctuation and timestamp tokens, and continues with tokens for the newly arrived audio."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n_sessions):
+        ref_text = rng.integers(1000, TEXT_VOCAB, size=n_tokens)
+        ref = []
+        for t in ref_text:
+            ref.append(int(t))
+            if rng.random() < p_punct:
+                ref.append(int(rng.choice(PUNCT_IDS)))
+        a = int(rng.integers(0, trim_max + 1))
+        cur = [TEXT_VOCAB + 1 + int(rng.integers(0, 1500))]          # leading timestamp
+        for t in ref_text[a:]:
+            cur.append(int(t) if rng.random() >= p_substitute else int(rng.integers(1000, TEXT_VOCAB)))
+            if rng.random() < p_punct:
+                cur.append(int(rng.choice(PUNCT_IDS)))
+            if rng.random() < p_timestamp:
+                cur.append(TEXT_VOCAB + 1 + int(rng.integers(0, 1500)))
+        cur += [int(t) for t in rng.integers(1000, TEXT_VOCAB, size=int(rng.integers(0, new_max + 1)))]
+        out.append((np.asarray(ref, np.int32), np.asarray(cur, np.int32)))
+    return out
+
+
 def draw_lengths_uniform(n: int, lo_s: float, hi_s: float, seed: int) -> List[int]:
     u = np.random.default_rng(seed).random(n)
     return [int(round(FRAMES_PER_SECOND * (lo_s + (hi_s - lo_s) * x))) for x in u]

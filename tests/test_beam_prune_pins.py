@@ -95,3 +95,16 @@ def test_beam_is_one_until_a_single_fallback_and_full_afterwards():
 def test_beam_size_one_has_nothing_to_prune():
     beams, _ = P.run_session(1, [1, 2, 3], SPECIAL_FROM, PUNCT, [9, 9, 9])
     assert beams == [1, 1, 1] and P.summary(1, beams)["reduce_ratio"] == 0.0
+
+
+def test_exempt_tokens_inside_the_reference_do_not_matter_either():
+    rng = np.random.default_rng(4)
+    for _ in range(50):
+        ref = _random_session(rng, 30)
+        tok = ref[int(rng.integers(0, 10)):] + [int(t) for t in rng.integers(0, 80, size=5)]
+        mixed_ref = []
+        for t in ref:
+            while rng.random() < 0.3:
+                mixed_ref.append(int(rng.choice([90, 91, 100, 160])))
+            mixed_ref.append(t)
+        assert P.run_session(BEAM, ref, SPECIAL_FROM, PUNCT, tok) == P.run_session(BEAM, mixed_ref, SPECIAL_FROM, PUNCT, tok)
