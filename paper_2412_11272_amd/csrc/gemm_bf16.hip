@@ -418,8 +418,24 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     // (PW * 4 bytes per row) per pass
     constexpr int PW = TN >= 64 ? 64 : TN;         // features per pass
     constexpr int RB = PW * 4, CPR = RB / 16, RPI = 64 / CPR;
+    const int rr = lane / CPR, c = lane % CPR;
+    // The residual values a lane will update are requested well before they are needed, so that their
+    // memory latency runs under the LDS transposition (and under the previous pass) instead of once per
+    // row: half of a pass's rows before its staging writes, the other half right after them (when that
+    // pass's accumulators are dead), and the first half of the NEXT pass before this pass's stores.
+    constexpr int NIT = TM / RPI, NPS = TN / PW;
+    f32x4 res[2][NIT];
+    auto fetch_res = [&](int ps, int it) {
+      int m = mw0 + it * RPI + rr;
+      m = m < p.M ? m : p.M - 1;
+      res[ps & 1][it] = *(const f32x4 *)((const float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
+    };
+    if (EPI == EPI_BIAS_RESID) {
 #pragma unroll
-    for (int ps = 0; ps < TN / PW; ++ps) {
+      for (int it = 0; it < NIT / 2; ++it) fetch_res(0, it);
+    }
+#pragma unroll
+    for (int ps = 0; ps < NPS; ++ps) {
 #pragma unroll
       for (int i = 0; i < IM; ++i) {
         const int r = i * 32 + l32;
@@ -438,24 +454,27 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
           }
         }
       }
-      __builtin_amdgcn_s_waitcnt(0xC07F);
-      const int rr = lane / CPR, c = lane % CPR;
+      if (EPI == EPI_BIAS_RESID) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int it = 0; it < TM / RPI; ++it) {
-        const int r = it * RPI + rr;
-        const f32x4 v = *(const f32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
-        const int m = mw0 + r;
-        if (m < p.M) {
-          f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
-          if (EPI == EPI_BIAS_RESID) {
-            f32x4 x = *o;
+        for (int it = NIT / 2; it < NIT; ++it) fetch_res(ps, it);
+        if (ps + 1 < NPS) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x[e] += v[e];
-            *o = x;
-          } else {
-            *o = v;
-          }
+          for (int it = 0; it < NIT / 2; ++it) fetch_res(ps + 1, it);
         }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int r = it * RPI + rr;
+        f32x4 v = *(const f32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
+        const int m = mw0 + r;
+        if (EPI == EPI_BIAS_RESID) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += res[ps & 1][it][e];
+        }
+        if (m < p.M) *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4) = v;
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);          // reads done before the next pass overwrites the slice
     }
