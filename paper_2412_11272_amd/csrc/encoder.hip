@@ -44,8 +44,17 @@ struct LayerDev {
 
 }  // namespace
 
+constexpr int kMaxLanes = 4;
+
 struct wf_encoder : DevCtx {
   wf_config cfg{};
+  // Lanes: the batch is cut into contiguous groups of streams that run the whole layer sequence on
+  // streams of their own, so that one group's bandwidth-bound kernels and GEMM tails overlap the other's
+  // matrix work.  Lane 0 is the caller's stream.
+  int n_lanes = 2;
+  hipStream_t lane_stream[kMaxLanes] = {};
+  hipEvent_t lane_done[kMaxLanes] = {};
+  hipEvent_t fork_evt = nullptr;
   int k1p = 0;                          // padded reduction length of the first convolution
   int64_t max_tokens = 0, max_work = 0, max_pos = 0;
   // weights
@@ -150,6 +159,11 @@ int wf_kernel_class_count(void) { return KC_COUNT; }
 void wf_encoder_destroy(wf_encoder *e) {
   if (!e) return;
   release(e);
+  for (int g = 1; g < kMaxLanes; ++g) {
+    if (e->lane_stream[g]) (void)hipStreamDestroy(e->lane_stream[g]);
+    if (e->lane_done[g]) (void)hipEventDestroy(e->lane_done[g]);
+  }
+  if (e->fork_evt) (void)hipEventDestroy(e->fork_evt);
   delete e;
 }
 
@@ -238,6 +252,11 @@ static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w)
   e->idx_ints = 4 * ((int64_t)cfg->max_streams + 1) + 2 * e->max_work;
   if ((rc = dev_alloc(e, (void **)&e->idx_dev, (size_t)e->idx_ints * 4))) return rc;
   if ((rc = staging_create(e, (size_t)e->idx_ints))) return rc;
+  for (int g = 1; g < kMaxLanes; ++g) {
+    HIP_TRY(hipStreamCreateWithFlags(&e->lane_stream[g], hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&e->lane_done[g], hipEventDisableTiming));
+  }
+  HIP_TRY(hipEventCreateWithFlags(&e->fork_evt, hipEventDisableTiming));
   HIP_TRY(hipDeviceSynchronize());
   return WF_OK;
 }
@@ -293,7 +312,25 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     return fail(WF_E_CAPACITY, "batch produces %d tokens but out_capacity_tokens = %lld", M, (long long)out_capacity_tokens);
   memcpy(h_off, frame_offset, (size_t)B * 4);
   memcpy(h_nf, n_frames, (size_t)B * 4);
-  const int n_work = build_work(h_cu_seq, B, attention_q_tile(), h_work);
+  // ---- lanes: contiguous groups of streams with about the same number of tokens each
+  int n_lanes = std::min(std::min(e->n_lanes, B), std::max(1, M / 4096));
+  if (!e->bf16) n_lanes = 1;             // the fp32 debug attention walks every row of the batch
+  int lane_b[kMaxLanes + 1], lane_w0[kMaxLanes + 1];
+  lane_b[0] = 0;
+  lane_w0[0] = 0;
+  {
+    int b = 0;
+    for (int g = 0; g < n_lanes; ++g) {
+      const int64_t target = (int64_t)M * (g + 1) / n_lanes;
+      int nb = b;
+      while (nb < B && (nb == b || h_cu_seq[nb + 1] <= target || g == n_lanes - 1)) ++nb;   // at least one stream each
+      if (B - nb < n_lanes - 1 - g) nb = B - (n_lanes - 1 - g);                                // leave one for every later lane
+      lane_b[g + 1] = nb;
+      lane_w0[g + 1] = lane_w0[g] + build_work(h_cu_seq + b, nb - b, attention_q_tile(), h_work + 2 * lane_w0[g], nullptr, b);
+      b = nb;
+    }
+  }
+  const int n_work = lane_w0[n_lanes];
   if (cu_seqlens_host) memcpy(cu_seqlens_host, h_cu_seq, (size_t)(B + 1) * 4);
 
   hipStream_t s = (hipStream_t)hip_stream;
@@ -304,9 +341,9 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
 
   const int d = c.d_model, f = c.d_mlp, C = c.n_mels;
   const int act_bf16 = e->bf16 ? 1 : 0;
-  const int es = e->es;
+  const size_t es = e->es;
 
-  // ---- a0: pack + hush append + row maps
+  // ---- a0: pack + hush append + row maps (whole batch, caller's stream)
   {
     PrepArgs a{};
     a.mel = mel_dev; a.hush = e->hush; a.packed = e->packed;
@@ -318,70 +355,78 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     hipError_t err = launch_prep(a, act_bf16, s);
     if (err != hipSuccess) return fail(WF_E_HIP, "prep launch: %s", hipGetErrorString(err));
   }
-  // ---- a1: conv1 + GELU as a GEMM over 3-frame windows
-  {
-    GemmArgs a{};
-    a.A = e->packed; a.W = e->conv1_w; a.bias = e->conv1_b; a.out = e->G;
-    a.M = TF; a.N = d; a.K = e->k1p; a.lda = C; a.ldo = d;
-    a.row_src = e->frame_src; a.row_flags = e->frame_flags; a.C = C;
-    if ((rc = run_gemm(e, s, KC_CONV1, a, A_CONV3, EPI_BIAS_GELU, 3 * C, es, TF, C))) return rc;
-  }
-  // ---- a2: conv2 (stride 2) + GELU + positions -> fp32 residual stream
-  {
-    GemmArgs a{};
-    a.A = e->G; a.W = e->conv2_w; a.bias = e->conv2_b; a.out = e->x;
-    a.M = M; a.N = d; a.K = 3 * d; a.lda = d; a.ldo = d;
-    a.row_src = e->tok_src; a.row_flags = e->tok_flags; a.C = d;
-    a.pos = e->pos; a.row_pos = e->tok_pos;
-    if ((rc = run_gemm(e, s, KC_CONV2, a, A_CONV3, EPI_BIAS_GELU_POS, 3 * d, 4, TF, d))) return rc;
-  }
-  // ---- transformer blocks
-  double attn_flops = 0.0;
-  for (int i = 0; i < B; ++i) {
-    const double L = h_cu_seq[i + 1] - h_cu_seq[i];
-    attn_flops += 4.0 * L * L * d;
-  }
-  for (int l = 0; l < c.n_layers; ++l) {
-    const LayerDev &w = e->layers[l];
-    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln1_g, w.ln1_b, e->u, act_bf16, M, d, c.ln_eps))) return rc;
-    {
+  if (n_lanes > 1) HIP_TRY(hipEventRecord(e->fork_evt, s));
+
+  // ---- a1 .. a9 for the streams [b0, b1) on stream ls
+  auto run_lane = [&](hipStream_t ls, int b0, int b1, const int32_t *work, int nw) -> int {
+    const int f0 = h_cu_frames[b0], Fg = h_cu_frames[b1] - f0;      // frames of the group
+    const int r0 = h_cu_seq[b0], Mg = h_cu_seq[b1] - r0;            // tokens of the group
+    const int Bg = b1 - b0;
+    char *G = (char *)e->G + (size_t)f0 * d * es;
+    float *x = e->x + (size_t)r0 * d;
+    char *u = (char *)e->u + (size_t)r0 * d * es;
+    char *qkv = (char *)e->qkv + (size_t)r0 * 3 * d * es;
+    char *hbuf = (char *)e->h + (size_t)r0 * f * es;
+    int rc;
+    {   // a1: conv1 + GELU as a GEMM over 3-frame windows (row maps hold absolute rows of the packed input)
       GemmArgs a{};
-      a.A = e->u; a.W = w.wqkv; a.bias = w.bqkv; a.out = e->qkv;
-      a.M = M; a.N = 3 * d; a.K = d; a.lda = d; a.ldo = 3 * d;
-      if ((rc = run_gemm(e, s, KC_QKV, a, A_PLAIN, EPI_BIAS, d, es, M, d))) return rc;
+      a.A = e->packed; a.W = e->conv1_w; a.bias = e->conv1_b; a.out = G;
+      a.M = Fg; a.N = d; a.K = e->k1p; a.lda = C; a.ldo = d;
+      a.row_src = e->frame_src + f0; a.row_flags = e->frame_flags + f0; a.C = C;
+      if ((rc = run_gemm(e, ls, KC_CONV1, a, A_CONV3, EPI_BIAS_GELU, 3 * C, (int)es, Fg, C))) return rc;
     }
-    {
-      AttnArgs a{};
-      a.q = e->qkv; a.k = (const char *)e->qkv + (size_t)d * es; a.v = (const char *)e->qkv + (size_t)2 * d * es;
-      a.ldq = a.ldkv = 3 * d; a.out = e->u; a.cu_q = a.cu_kv = d_cu_seq; a.work = d_work;
-      a.n_work = n_work; a.n_heads = c.n_heads; a.d_model = d; a.B = B; a.M = M;
-      a.scale = 0.125f;
-      Scope sc(e, s, KC_ATTN, attn_flops, (double)M * 4 * d * es);
-      hipError_t err = e->bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s);
-      if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
-    }
-    {
+    {   // a2: conv2 (stride 2) + GELU + positions -> fp32 residual stream
       GemmArgs a{};
-      a.A = e->u; a.W = w.wo; a.bias = w.bo; a.out = e->x;
-      a.M = M; a.N = d; a.K = d; a.lda = d; a.ldo = d;
-      if ((rc = run_gemm(e, s, KC_OUT, a, A_PLAIN, EPI_BIAS_RESID, d, 4, M, d))) return rc;
+      a.A = e->G; a.W = e->conv2_w; a.bias = e->conv2_b; a.out = x;
+      a.M = Mg; a.N = d; a.K = 3 * d; a.lda = d; a.ldo = d;
+      a.row_src = e->tok_src + r0; a.row_flags = e->tok_flags + r0; a.C = d;
+      a.pos = e->pos; a.row_pos = e->tok_pos + r0;
+      if ((rc = run_gemm(e, ls, KC_CONV2, a, A_CONV3, EPI_BIAS_GELU_POS, 3 * d, 4, Fg, d))) return rc;
     }
-    if ((rc = run_ln(e, s, KC_LN, e->x, w.ln2_g, w.ln2_b, e->u, act_bf16, M, d, c.ln_eps))) return rc;
-    {
-      GemmArgs a{};
-      a.A = e->u; a.W = w.w1; a.bias = w.b1; a.out = e->h;
-      a.M = M; a.N = f; a.K = d; a.lda = d; a.ldo = f;
-      if ((rc = run_gemm(e, s, KC_FC1, a, A_PLAIN, EPI_BIAS_GELU, d, es, M, d))) return rc;
+    double attn_flops = 0.0;
+    for (int i = b0; i < b1; ++i) {
+      const double L = h_cu_seq[i + 1] - h_cu_seq[i];
+      attn_flops += 4.0 * L * L * d;
     }
-    {
-      GemmArgs a{};
-      a.A = e->h; a.W = w.w2; a.bias = w.b2; a.out = e->x;
-      a.M = M; a.N = d; a.K = f; a.lda = f; a.ldo = d;
-      if ((rc = run_gemm(e, s, KC_FC2, a, A_PLAIN, EPI_BIAS_RESID, f, 4, M, f))) return rc;
+    for (int l = 0; l < c.n_layers; ++l) {
+      const LayerDev &w = e->layers[l];
+      if ((rc = run_ln(e, ls, KC_LN, x, w.ln1_g, w.ln1_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
+      if ((rc = run_linear(e, ls, KC_QKV, u, d, w.wqkv, w.bqkv, qkv, 3 * d, Mg, 3 * d, d, EPI_BIAS))) return rc;
+      {
+        AttnArgs a{};   // q, k, v and out are addressed through the absolute prefix sums, so the bases stay whole-batch
+        a.q = e->qkv; a.k = (const char *)e->qkv + (size_t)d * es; a.v = (const char *)e->qkv + (size_t)2 * d * es;
+        a.ldq = a.ldkv = 3 * d; a.out = e->u; a.cu_q = a.cu_kv = d_cu_seq; a.work = work;
+        a.n_work = nw; a.n_heads = c.n_heads; a.d_model = d; a.B = B; a.M = M;
+        a.scale = 0.125f;
+        Scope sc(e, ls, KC_ATTN, attn_flops, (double)Mg * 4 * d * es);
+        hipError_t err = e->bf16 ? launch_attention_bf16(a, ls) : launch_attention_f32(a, ls);
+        if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
+      }
+      if ((rc = run_linear(e, ls, KC_OUT, u, d, w.wo, w.bo, x, d, Mg, d, d, EPI_BIAS_RESID))) return rc;
+      if ((rc = run_ln(e, ls, KC_LN, x, w.ln2_g, w.ln2_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
+      if ((rc = run_linear(e, ls, KC_FC1, u, d, w.w1, w.b1, hbuf, f, Mg, f, d, EPI_BIAS_GELU))) return rc;
+      if ((rc = run_linear(e, ls, KC_FC2, hbuf, f, w.w2, w.b2, x, d, Mg, d, f, EPI_BIAS_RESID))) return rc;
     }
+    // a9: final LayerNorm straight into the caller's buffer
+    char *out = (char *)out_dev + (size_t)r0 * d * (out_dtype == WF_DTYPE_BF16 ? 2 : 4);
+    (void)Bg;
+    return run_ln(e, ls, KC_LNF, x, e->lnf_g, e->lnf_b, out, out_dtype == WF_DTYPE_BF16, Mg, d, c.ln_eps);
+  };
+
+  for (int g = n_lanes - 1; g >= 0; --g) {                 // the caller's own lane is enqueued last
+    hipStream_t ls = g == 0 ? s : e->lane_stream[g];
+    if (g > 0) HIP_TRY(hipStreamWaitEvent(ls, e->fork_evt, 0));
+    if ((rc = run_lane(ls, lane_b[g], lane_b[g + 1], d_work + 2 * lane_w0[g], lane_w0[g + 1] - lane_w0[g]))) return rc;
+    if (g > 0) HIP_TRY(hipEventRecord(e->lane_done[g], ls));
   }
-  // ---- a9: final LayerNorm straight into the caller's buffer
-  if ((rc = run_ln(e, s, KC_LNF, e->x, e->lnf_g, e->lnf_b, out_dev, out_dtype == WF_DTYPE_BF16, M, d, c.ln_eps))) return rc;
+  for (int g = 1; g < n_lanes; ++g) HIP_TRY(hipStreamWaitEvent(s, e->lane_done[g], 0));
+  return WF_OK;
+}
+
+int wf_encoder_set_lanes(wf_encoder *e, int32_t n_lanes) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  if (n_lanes < 1 || n_lanes > kMaxLanes) return fail(WF_E_INVALID_ARG, "n_lanes = %d, need 1 .. %d", n_lanes, (int)kMaxLanes);
+  e->n_lanes = n_lanes;
   return WF_OK;
 }
 

@@ -222,7 +222,7 @@ inline int run_ln(DevCtx *e, hipStream_t s, int cls, const float *x, const float
 // Attention work list: one item per (stream, block of q_tile queries), longest streams first so the
 // expensive items are scheduled before the cheap ones fill in.  cost[i] orders the streams (NULL: the
 // query count).
-inline int build_work(const int32_t *cu_q, int B, int q_tile, int32_t *work, const int64_t *cost = nullptr) {
+inline int build_work(const int32_t *cu_q, int B, int q_tile, int32_t *work, const int64_t *cost = nullptr, int stream_base = 0) {
   std::vector<std::pair<int64_t, int>> order(B);
   for (int i = 0; i < B; ++i) order[i] = {cost ? cost[i] : (int64_t)(cu_q[i + 1] - cu_q[i]), i};
   std::stable_sort(order.begin(), order.end(),
@@ -231,7 +231,7 @@ inline int build_work(const int32_t *cu_q, int B, int q_tile, int32_t *work, con
   for (const auto &o : order) {
     const int Lq = cu_q[o.second + 1] - cu_q[o.second];
     for (int q0 = 0; q0 < Lq; q0 += q_tile) {
-      work[2 * n] = o.second;
+      work[2 * n] = o.second + stream_base;     // cu_q points at the first of the B streams; ids stay absolute
       work[2 * n + 1] = q0;
       ++n;
     }

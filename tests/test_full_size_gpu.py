@@ -23,6 +23,11 @@ def _run(name):
         out2, _ = enc.encode(mel, offs, nf, out_dtype=torch.bfloat16)
         torch.cuda.synchronize()
         assert torch.equal(out, out2)                     # deterministic run to run
+        for lanes in (1, 3):                              # and independent of how the batch is cut into lanes
+            enc.set_lanes(lanes)
+            out3, _ = enc.encode(mel, offs, nf, out_dtype=torch.bfloat16)
+            torch.cuda.synchronize()
+            assert torch.equal(out, out3), lanes
         return wl, w, hush, mels, out.float().cpu().numpy(), cu
     finally:
         enc.close()
