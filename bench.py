@@ -218,17 +218,27 @@ def main():
                     help="lanes of the encoder in the timed region (0 = the library's default); per-kernel durations are "
                          "always measured with one lane, i.e. with kernels running one at a time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--encoder-only", action="store_true",
+                    help="time the encoder hot path only; by default the legs of the other rows (front end, decoder-side "
+                         "steps, round driver, beam pruning) run after it and are reported in objects of their own")
     ap.add_argument("--frontend", action="store_true",
-                    help="also time the raw-audio log-mel front end on audio of the same lengths (reported separately)")
+                    help="with --encoder-only: also time the raw-audio log-mel front end on audio of the same lengths")
     ap.add_argument("--prefill", action="store_true",
-                    help="also time the decoder-side steps on the encoder states of the same batch (reported separately)")
-    ap.add_argument("--rounds", type=int, default=0,
-                    help="also run this many processing rounds per step length through the round driver (reported separately)")
-    ap.add_argument("--beam-sessions", type=int, default=0,
-                    help="also run the beam-pruning state machine over this many synthetic decoding sessions (host only)")
+                    help="with --encoder-only: also time the decoder-side steps on the encoder states of the same batch")
+    ap.add_argument("--rounds", type=int, default=-1,
+                    help="processing rounds per step length through the round driver (default 8; 0 with --encoder-only)")
+    ap.add_argument("--beam-sessions", type=int, default=-1,
+                    help="synthetic decoding sessions for the beam-pruning state machine, host only (default 2000; 0 with --encoder-only)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
+    legs = not args.encoder_only and args.workload == "cfg5"
+    args.frontend = args.frontend or legs
+    args.prefill = args.prefill or legs
+    if args.rounds < 0:
+        args.rounds = 8 if legs else 0
+    if args.beam_sessions < 0:
+        args.beam_sessions = 2000 if legs else 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams shard across GPUs without collectives; "
               "no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
