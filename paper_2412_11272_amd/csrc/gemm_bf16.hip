@@ -242,7 +242,6 @@ template <int BM, int BN, int WM, int WN, int EPI, int SMEM>   // SMEM: bytes of
 __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
-  constexpr int IM = TM / 32, IN = TN / 32;
   constexpr int XL = BM / 8 / NW;    // load instructions per wave for the activation tile (8 rows each)
   constexpr int WL = BN / 8 / NW;
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TN % 32 == 0, "tile/waves mismatch");
@@ -254,7 +253,6 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
-  const int l32 = lane & 31, lg = lane >> 5;
 
   // lane -> row within the 8-row group written by one load instruction; the chunk it fetches is the
   // one that belongs at its LDS slot: (lane & 7) ^ swizzle(row)
@@ -291,87 +289,113 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
                                        (lds_void *)(sW + stage * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
   };
 
-  f32x16 acc[IM][IN];
+  // Accumulators: v_mfma_f32_16x16x32_bf16 blocks, TB token blocks x FB feature blocks of 16 x 16.  With
+  // the weight fragment as first operand a lane holds, per block, token (lane % 16) and features
+  // 4 * (lane / 16) + (0..3).  (This instruction shape does the same work per cycle as the 32x32x16 one but
+  // draws less power: on random operands a register-only loop sustains 1.97 against 1.76 PFLOP/s.)
+  constexpr int TB = TM / 16, FB = TN / 16, FBH = FB / 2;
+  static_assert(TM % 16 == 0 && TN % 32 == 0, "wave tile must be a multiple of 16 x 32");
+  f32x4 acc[TB][FB];
 #pragma unroll
-  for (int i = 0; i < IM; ++i)
+  for (int i = 0; i < TB; ++i)
 #pragma unroll
-    for (int j = 0; j < IN; ++j)
+    for (int j = 0; j < FB; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const int nk = p.K / BK;
-  const int xrow0 = (wm * TM + l32) * 128;
-  const int wrow0 = (wn * TN + l32) * 128;
-  const int sw = (l32 >> 1) & 7;
+  const int l16 = lane & 15, lq = lane >> 4;       // row inside a 16-row block; which 8 of the 32 reduction indices
+  const int xrow0 = (wm * TM + l16) * 128;
+  const int wrow0 = (wn * TN + l16) * 128;
+  const int sw = (l16 >> 1) & 7;
 
-  // Main loop.  Fragments are double-buffered in registers: the reads of k-step s+1 are issued, then the
-  // 8 MFMAs of k-step s run while they are in flight.  The one barrier per K step of 64 sits right after
-  // the LAST fragment read of the current tile: at that point (a) every wave has finished reading this
-  // LDS stage, so the loads of tile kt+2 may overwrite it, and (b) every wave has seen its own loads of
-  // tile kt+1 land, so its first fragments can be read under the MFMAs of k-step 3 -- the matrix pipe
-  // never drains at the barrier.  The two waves that share a SIMD issue their global loads at
-  // different points (before / after those MFMAs), so one keeps the matrix pipe busy while the other
-  // is held up handing loads to the memory pipeline.
+  // Main loop.  A 64-deep LDS stage is two reduction steps of 32 (t = 0, 1); each step is split into the
+  // lower and the upper half of the wave's feature blocks, so that a sub-step is TB*FBH MFMAs on one set of
+  // activation fragments (xf) and one set of weight fragments (wlo / whi).  Fragments are prefetched one
+  // sub-step ahead: under the MFMAs of (t, lo) the upper weight fragments of step t are read, under those
+  // of (t, hi) the activation and lower weight fragments of step t+1.  The one barrier per stage sits right
+  // after the LAST fragment read of the current stage: at that point (a) every wave has finished reading
+  // this stage, so the loads of tile kt+2 may overwrite it, and (b) every wave has seen its own loads of
+  // tile kt+1 land, so its first fragments can be read under the MFMAs of the last sub-step -- the matrix
+  // pipe never drains at the barrier.  The two waves that share a SIMD issue their global loads at
+  // different points (before / after those MFMAs), so one keeps the matrix pipe busy while the other is
+  // held up handing loads to the memory pipeline.
   const bool early = (wave < NW / 2) || NW < 8;
-  bf16x8 wf[2][IN], xf[2][IM];
-  auto rd = [&](int stage, int ks, int buf) {
-    const unsigned char *cx = sX + stage * BM * 128 + xrow0;
-    const unsigned char *cw = sW + stage * BN * 128 + wrow0;
-    const int choff = ((2 * ks + lg) ^ sw) << 4;
+  bf16x8 xf[2][TB], wlo[FBH], whi[FBH];
+  auto rd_x = [&](int stage, int t, int buf) {
+    const unsigned char *cx = sX + stage * BM * 128 + xrow0 + (((4 * t + lq) ^ sw) << 4);
 #pragma unroll
-    for (int j = 0; j < IN; ++j) wf[buf][j] = *(const bf16x8 *)(cw + j * 32 * 128 + choff);
-#pragma unroll
-    for (int i = 0; i < IM; ++i) xf[buf][i] = *(const bf16x8 *)(cx + i * 32 * 128 + choff);
+    for (int i = 0; i < TB; ++i) xf[buf][i] = *(const bf16x8 *)(cx + i * 16 * 128);
   };
-  auto mm = [&](int buf) {
+  auto rd_w = [&](int stage, int t, int half, bf16x8 (&dst)[FBH]) {
+    const unsigned char *cw = sW + stage * BN * 128 + wrow0 + half * FBH * 16 * 128 + (((4 * t + lq) ^ sw) << 4);
 #pragma unroll
-    for (int i = 0; i < IM; ++i)
-#pragma unroll
-      for (int j = 0; j < IN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < FBH; ++j) dst[j] = *(const bf16x8 *)(cw + j * 16 * 128);
   };
-  // One k-step: lgkmcnt(0) is placed BEFORE the next reads are issued, so that it only waits for the
-  // older ones; then the scheduler is told to alternate one MFMA with one LDS read, which hides the
-  // issue slots of the reads under the matrix pipe's 32-cycle occupancy per MFMA.
-#define WF_STEP(stage, ks_next, buf_next, buf_cur)                                                     \
-  __builtin_amdgcn_s_waitcnt(0xC07F);                                                                 \
-  __builtin_amdgcn_sched_barrier(0);                                                                  \
-  rd(stage, ks_next, buf_next);                                                                       \
-  mm(buf_cur);                                                                                        \
-  _Pragma("unroll") for (int q_ = 0; q_ < IM + IN; ++q_) {                                            \
+  auto mm = [&](int half, const bf16x8 (&w)[FBH], int buf) {
+#pragma unroll
+    for (int i = 0; i < TB; ++i)
+#pragma unroll
+      for (int j = 0; j < FBH; ++j)
+        acc[i][half * FBH + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[j], xf[buf][i], acc[i][half * FBH + j], 0, 0, 0);
+  };
+  // Scheduling hint for a sub-step with NRD fragment reads: alternate one MFMA with one LDS read, then the
+  // remaining MFMAs -- the issue slots of the reads hide under the matrix pipe's occupancy.
+#define WF_SCHED(NRD)                                                                                  \
+  _Pragma("unroll") for (int q_ = 0; q_ < (NRD); ++q_) {                                              \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                \
   }                                                                                                   \
-  __builtin_amdgcn_sched_group_barrier(0x008, (IM * IN > IM + IN ? IM * IN - (IM + IN) : 0), 0);      \
+  __builtin_amdgcn_sched_group_barrier(0x008, (TB * FBH > (NRD) ? TB * FBH - (NRD) : 0), 0);          \
   __builtin_amdgcn_sched_barrier(0)
 
   issue(0);
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
   __builtin_amdgcn_s_barrier();
   if (1 < nk) issue(1);
-  rd(0, 0, 0);
+  rd_x(0, 0, 0);
+  rd_w(0, 0, 0, wlo);
   for (int kt = 0; kt < nk; ++kt) {
     const int st = kt & 1;
     __builtin_amdgcn_sched_barrier(0);
-    WF_STEP(st, 1, 1, 0);
-    WF_STEP(st, 2, 0, 1);
-    WF_STEP(st, 3, 1, 0);
+    // (t = 0, lo): read the upper weight fragments of step 0
+    __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0), placed BEFORE the next reads so it only waits for older ones
+    __builtin_amdgcn_sched_barrier(0);
+    rd_w(st, 0, 1, whi);
+    mm(0, wlo, 0);
+    WF_SCHED(FBH);
+    // (t = 0, hi): read the activation and lower weight fragments of step 1
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_sched_barrier(0);
+    rd_x(st, 1, 1);
+    rd_w(st, 1, 0, wlo);
+    mm(1, whi, 0);
+    WF_SCHED(TB + FBH);
+    // (t = 1, lo): read the upper weight fragments of step 1
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_sched_barrier(0);
+    rd_w(st, 1, 1, whi);
+    mm(0, wlo, 1);
+    WF_SCHED(FBH);
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): stage st fully read, my part of tile kt+1 landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     if (kt + 2 < nk && early) issue(kt + 2);
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < nk) rd(st ^ 1, 0, 0);
+    if (kt + 1 < nk) {
+      rd_x(st ^ 1, 0, 0);
+      rd_w(st ^ 1, 0, 0, wlo);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    mm(1);
+    mm(1, whi, 1);                                 // (t = 1, hi)
     __builtin_amdgcn_sched_barrier(0);
     if (kt + 2 < nk && !early) issue(kt + 2);
     __builtin_amdgcn_sched_barrier(0);
   }
-#undef WF_STEP
+#undef WF_SCHED
 
   // ---- epilogue.  The accumulator layout gives a lane 4 consecutive features of ONE token, which would
-  // make every store instruction touch 32 different rows.  Each wave therefore transposes its sub-tile
+  // make every store instruction touch 16 different rows.  Each wave therefore transposes its sub-tile
   // through its own 16 KB slice of the (now idle) LDS stages and writes whole 128/256-byte row
   // segments: 16-byte chunk c of row r sits at chunk position c ^ (r & (CPR-1)).
   __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -383,24 +407,21 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     constexpr int RB = TN * 2;                     // row bytes (bf16)
     constexpr int CPR = RB / 16;                   // 16-byte chunks per row
 #pragma unroll
-    for (int i = 0; i < IM; ++i) {
-      const int r = i * 32 + l32;
+    for (int i = 0; i < TB; ++i) {
+      const int r = i * 16 + l16;
 #pragma unroll
-      for (int j = 0; j < IN; ++j) {
+      for (int j = 0; j < FB; ++j) {
+        const int nl = j * 16 + lq * 4;            // feature inside the wave's sub-tile
+        const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
+        f32x4 v;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int nl = j * 32 + g * 8 + lg * 4;  // feature inside the wave's sub-tile
-          const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
-          f32x4 v;
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e] + b[e];
+        if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
-          if (EPI == EPI_BIAS_GELU) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
-          }
-          const int u = nl >> 2;                   // 8-byte unit inside the row
-          *(bf16x4 *)(stg + r * RB + ((((u >> 1) ^ (r & (CPR - 1))) << 4) | ((u & 1) << 3))) = to_bf16x4(v);
+          for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
         }
+        const int u = nl >> 2;                     // 8-byte unit inside the row
+        *(bf16x4 *)(stg + r * RB + ((((u >> 1) ^ (r & (CPR - 1))) << 4) | ((u & 1) << 3))) = to_bf16x4(v);
       }
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): the wave's own LDS writes have landed
@@ -437,21 +458,18 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 #pragma unroll
     for (int ps = 0; ps < NPS; ++ps) {
 #pragma unroll
-      for (int i = 0; i < IM; ++i) {
-        const int r = i * 32 + l32;
+      for (int i = 0; i < TB; ++i) {
+        const int r = i * 16 + l16;
 #pragma unroll
-        for (int jj = 0; jj < PW / 32; ++jj) {
-          const int j = ps * (PW / 32) + jj;
+        for (int jj = 0; jj < PW / 16; ++jj) {
+          const int j = ps * (PW / 16) + jj;
+          const int nl = j * 16 + lq * 4;
+          const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
+          f32x4 v;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int nl = j * 32 + g * 8 + lg * 4;
-            const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
-            f32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + b[e];
-            const int ch = (nl % PW) >> 2;         // 16-byte chunk inside the pass
-            *(f32x4 *)(stg + r * RB + ((ch ^ (r & (CPR - 1))) << 4)) = v;
-          }
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e] + b[e];
+          const int ch = (nl % PW) >> 2;           // 16-byte chunk inside the pass
+          *(f32x4 *)(stg + r * RB + ((ch ^ (r & (CPR - 1))) << 4)) = v;
         }
       }
       if (EPI == EPI_BIAS_RESID) {
