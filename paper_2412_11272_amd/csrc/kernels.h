@@ -35,6 +35,7 @@ struct GemmArgs {
   int32_t lda, ldo;
   // work-unit split of the direct-load GEMM (set by its launcher): full tiles, then half-width units
   int32_t n_full, n_half, full_per_xcd, half_per_xcd;
+  int32_t group_n;          // tiles walk column groups of this many tile columns (>= tiles per row: plain row-major)
   // A_CONV3 only
   const int32_t *row_src;
   const int32_t *row_flags;
