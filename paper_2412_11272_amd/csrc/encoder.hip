@@ -48,10 +48,10 @@ constexpr int kMaxLanes = 4;
 
 struct wf_encoder : DevCtx {
   wf_config cfg{};
-  // Lanes: the batch is cut into contiguous groups of streams that run the whole layer sequence on
-  // streams of their own, so that one group's bandwidth-bound kernels and GEMM tails overlap the other's
-  // matrix work.  Lane 0 is the caller's stream.
-  int n_lanes = 2;
+  // Lanes (optional, wf_encoder_set_lanes): the batch is cut into contiguous groups of streams that run the
+  // whole layer sequence on streams of their own, so that one group's bandwidth-bound kernels and GEMM tails
+  // overlap the other's matrix work.  Lane 0 is the caller's stream.
+  int n_lanes = 1;
   hipStream_t lane_stream[kMaxLanes] = {};
   hipEvent_t lane_done[kMaxLanes] = {};
   hipEvent_t fork_evt = nullptr;
