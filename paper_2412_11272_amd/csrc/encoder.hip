@@ -243,7 +243,8 @@ static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w)
   if ((rc = dev_alloc(e, (void **)&e->x, (size_t)Mx * d * 4))) return rc;
   if ((rc = dev_alloc(e, &e->u, (size_t)Mx * d * e->es))) return rc;
   if ((rc = dev_alloc(e, &e->qkv, (size_t)Mx * 3 * d * e->es))) return rc;
-  if ((rc = dev_alloc(e, &e->h, (size_t)Mx * f * e->es))) return rc;
+  // the MLP's hidden activations are kept in panel layout on the bf16 path: whole 256-row panels per lane
+  if ((rc = dev_alloc(e, &e->h, (size_t)(Mx + 256 * kMaxLanes) * f * e->es))) return rc;
   if ((rc = dev_alloc(e, (void **)&e->frame_src, (size_t)F * 4))) return rc;
   if ((rc = dev_alloc(e, (void **)&e->frame_flags, (size_t)F * 4))) return rc;
   if ((rc = dev_alloc(e, (void **)&e->tok_src, (size_t)Mx * 4))) return rc;
@@ -358,7 +359,7 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
   if (n_lanes > 1) HIP_TRY(hipEventRecord(e->fork_evt, s));
 
   // ---- a1 .. a9 for the streams [b0, b1) on stream ls
-  auto run_lane = [&](hipStream_t ls, int b0, int b1, const int32_t *work, int nw) -> int {
+  auto run_lane = [&](hipStream_t ls, int b0, int b1, const int32_t *work, int nw, int64_t h_row0) -> int {
     const int f0 = h_cu_frames[b0], Fg = h_cu_frames[b1] - f0;      // frames of the group
     const int r0 = h_cu_seq[b0], Mg = h_cu_seq[b1] - r0;            // tokens of the group
     const int Bg = b1 - b0;
@@ -366,7 +367,8 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     float *x = e->x + (size_t)r0 * d;
     char *u = (char *)e->u + (size_t)r0 * d * es;
     char *qkv = (char *)e->qkv + (size_t)r0 * 3 * d * es;
-    char *hbuf = (char *)e->h + (size_t)r0 * f * es;
+    char *hbuf = (char *)e->h + (size_t)h_row0 * f * es;           // panel-aligned start of this lane's hidden activations
+    const int panels = e->bf16 ? 1 : 0;                            // the fp32 debug kernels keep everything row-major
     int rc;
     {   // a1: conv1 + GELU as a GEMM over 3-frame windows (row maps hold absolute rows of the packed input)
       GemmArgs a{};
@@ -404,8 +406,19 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
       }
       if ((rc = run_linear(e, ls, KC_OUT, u, d, w.wo, w.bo, x, d, Mg, d, d, EPI_BIAS_RESID))) return rc;
       if ((rc = run_ln(e, ls, KC_LN, x, w.ln2_g, w.ln2_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
-      if ((rc = run_linear(e, ls, KC_FC1, u, d, w.w1, w.b1, hbuf, f, Mg, f, d, EPI_BIAS_GELU))) return rc;
-      if ((rc = run_linear(e, ls, KC_FC2, hbuf, f, w.w2, w.b2, x, d, Mg, d, f, EPI_BIAS_RESID))) return rc;
+      {   // fc1 writes the hidden activations as [rows/256][f/64][256][64] panels: one contiguous 32 KB block per
+          // K step of fc2's activation operand (whose rows would otherwise be 2 f bytes apart in memory)
+        GemmArgs a{};
+        a.A = u; a.W = w.w1; a.bias = w.b1; a.out = hbuf; a.M = Mg; a.N = f; a.K = d; a.lda = d; a.ldo = f;
+        a.out_panels = panels;
+        if ((rc = run_gemm(e, ls, KC_FC1, a, A_PLAIN, EPI_BIAS_GELU, d, (int)es, Mg, d))) return rc;
+      }
+      {
+        GemmArgs a{};
+        a.A = hbuf; a.W = w.w2; a.bias = w.b2; a.out = x; a.M = Mg; a.N = d; a.K = f; a.lda = f; a.ldo = d;
+        a.a_panels = panels;
+        if ((rc = run_gemm(e, ls, KC_FC2, a, A_PLAIN, EPI_BIAS_RESID, f, 4, Mg, f))) return rc;
+      }
     }
     // a9: final LayerNorm straight into the caller's buffer
     char *out = (char *)out_dev + (size_t)r0 * d * (out_dtype == WF_DTYPE_BF16 ? 2 : 4);
@@ -413,10 +426,14 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     return run_ln(e, ls, KC_LNF, x, e->lnf_g, e->lnf_b, out, out_dtype == WF_DTYPE_BF16, Mg, d, c.ln_eps);
   };
 
+  int64_t h_row0[kMaxLanes + 1];                           // every lane's hidden activations start on a panel boundary
+  h_row0[0] = 0;
+  for (int g = 0; g < n_lanes; ++g)
+    h_row0[g + 1] = h_row0[g] + round_up(h_cu_seq[lane_b[g + 1]] - h_cu_seq[lane_b[g]], 256);
   for (int g = n_lanes - 1; g >= 0; --g) {                 // the caller's own lane is enqueued last
     hipStream_t ls = g == 0 ? s : e->lane_stream[g];
     if (g > 0) HIP_TRY(hipStreamWaitEvent(ls, e->fork_evt, 0));
-    if ((rc = run_lane(ls, lane_b[g], lane_b[g + 1], d_work + 2 * lane_w0[g], lane_w0[g + 1] - lane_w0[g]))) return rc;
+    if ((rc = run_lane(ls, lane_b[g], lane_b[g + 1], d_work + 2 * lane_w0[g], lane_w0[g + 1] - lane_w0[g], h_row0[g]))) return rc;
     if (g > 0) HIP_TRY(hipEventRecord(e->lane_done[g], ls));
   }
   for (int g = 1; g < n_lanes; ++g) HIP_TRY(hipStreamWaitEvent(s, e->lane_done[g], 0));

@@ -268,7 +268,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     const int lch = (lane & 7) ^ ((rt >> 1) & 7);
     int row = m0 + rt;
     row = row < p.M ? row : p.M - 1;              // rows past M are computed but never stored
-    xptr[i] = A + (size_t)row * p.lda + lch * 8;
+    xptr[i] = p.a_panels ? A + ((size_t)(row >> 8) * (p.K >> 6) << 14) + ((row & 255) << 6) + lch * 8   // panel layout
+                         : A + (size_t)row * p.lda + lch * 8;
   }
 #pragma unroll
   for (int i = 0; i < WL; ++i) {
@@ -280,9 +281,10 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   auto issue = [&](int kt) {
     const int stage = kt & 1;
     const int k0 = kt * BK;
+    const int ka = p.a_panels ? kt << 14 : k0;     // panel layout: the next 64-column chunk is 256 * 64 elements on
 #pragma unroll
     for (int i = 0; i < XL; ++i)
-      __builtin_amdgcn_global_load_lds((const glb_void *)(xptr[i] + k0),
+      __builtin_amdgcn_global_load_lds((const glb_void *)(xptr[i] + ka),
                                        (lds_void *)(sX + stage * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < WL; ++i)
@@ -433,7 +435,12 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       const int r = it * RPI + rr;
       const u32x4 v = *(const u32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
       const int m = mw0 + r;
-      if (m < p.M) *(u32x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nw0 + c * 8) = v;
+      if (m < p.M) {
+        const int n = nw0 + c * 8;
+        __bf16 *dst = p.out_panels ? (__bf16 *)p.out + ((((size_t)(m >> 8) * (p.N >> 6) + (n >> 6)) << 14) + ((m & 255) << 6) + (n & 63))
+                                   : (__bf16 *)p.out + (size_t)m * p.ldo + n;
+        *(u32x4 *)dst = v;
+      }
     }
   } else {
     // fp32 output: residual update in place (EPI_BIAS_RESID) or plain store (EPI_BIAS_F32), PW features
@@ -573,6 +580,7 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
   const bool big = use_large_tile(a);
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
+    if (a.out_panels && epi != EPI_BIAS && epi != EPI_BIAS_GELU) return hipErrorInvalidValue;   // bf16 results only
     switch (epi) {
       case EPI_BIAS:
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS>(a, s);

@@ -36,6 +36,10 @@ struct GemmArgs {
   // work-unit split of the direct-load GEMM (set by its launcher): full tiles, then half-width units
   int32_t n_full, n_half, full_per_xcd, half_per_xcd;
   int32_t group_n;          // tiles walk column groups of this many tile columns (>= tiles per row: plain row-major)
+  // Panel layout (direct-load GEMM only): instead of row-major, a matrix is stored as [rows/256][cols/64][256][64],
+  // i.e. every (256-row panel, 64-column chunk) is one contiguous 32 KB block -- exactly one K step of a
+  // tile's activation operand.  a_panels: A is read in that layout; out_panels: a bf16 result is written in it.
+  int32_t a_panels, out_panels;
   // A_CONV3 only
   const int32_t *row_src;
   const int32_t *row_flags;
