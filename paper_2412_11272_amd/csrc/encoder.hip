@@ -222,11 +222,18 @@ static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w)
     memcpy(bqkv.data(), s.bq, (size_t)d * 4);
     if (s.bk) memcpy(bqkv.data() + d, s.bk, (size_t)d * 4);
     memcpy(bqkv.data() + 2 * d, s.bv, (size_t)d * 4);
-    if ((rc = upload_w(e, &t.wqkv, wqkv))) return rc;
+    if (e->bf16) {     // the projection weights of the MFMA path live in panel layout
+      if ((rc = upload_w_panels(e, &t.wqkv, wqkv.data(), 3 * d, d))) return rc;
+      if ((rc = upload_w_panels(e, &t.wo, s.wo, d, d))) return rc;
+      if ((rc = upload_w_panels(e, &t.w1, s.w1, f, d))) return rc;
+      if ((rc = upload_w_panels(e, &t.w2, s.w2, d, f))) return rc;
+    } else {
+      if ((rc = upload_w(e, &t.wqkv, wqkv))) return rc;
+      if ((rc = upload_w(e, &t.wo, std::vector<float>(s.wo, s.wo + (size_t)d * d)))) return rc;
+      if ((rc = upload_w(e, &t.w1, std::vector<float>(s.w1, s.w1 + (size_t)f * d)))) return rc;
+      if ((rc = upload_w(e, &t.w2, std::vector<float>(s.w2, s.w2 + (size_t)d * f)))) return rc;
+    }
     if ((rc = upload_f32(e, &t.bqkv, bqkv.data(), bqkv.size()))) return rc;
-    if ((rc = upload_w(e, &t.wo, std::vector<float>(s.wo, s.wo + (size_t)d * d)))) return rc;
-    if ((rc = upload_w(e, &t.w1, std::vector<float>(s.w1, s.w1 + (size_t)f * d)))) return rc;
-    if ((rc = upload_w(e, &t.w2, std::vector<float>(s.w2, s.w2 + (size_t)d * f)))) return rc;
     if ((rc = upload_f32(e, &t.bo, s.bo, d))) return rc;
     if ((rc = upload_f32(e, &t.b1, s.b1, f))) return rc;
     if ((rc = upload_f32(e, &t.b2, s.b2, d))) return rc;
@@ -393,7 +400,12 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     for (int l = 0; l < c.n_layers; ++l) {
       const LayerDev &w = e->layers[l];
       if ((rc = run_ln(e, ls, KC_LN, x, w.ln1_g, w.ln1_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
-      if ((rc = run_linear(e, ls, KC_QKV, u, d, w.wqkv, w.bqkv, qkv, 3 * d, Mg, 3 * d, d, EPI_BIAS))) return rc;
+      {
+        GemmArgs a{};
+        a.A = u; a.W = w.wqkv; a.bias = w.bqkv; a.out = qkv; a.M = Mg; a.N = 3 * d; a.K = d; a.lda = d; a.ldo = 3 * d;
+        a.w_panels = panels;
+        if ((rc = run_gemm(e, ls, KC_QKV, a, A_PLAIN, EPI_BIAS, d, (int)es, Mg, d))) return rc;
+      }
       {
         AttnArgs a{};   // q, k, v and out are addressed through the absolute prefix sums, so the bases stay whole-batch
         a.q = e->qkv; a.k = (const char *)e->qkv + (size_t)d * es; a.v = (const char *)e->qkv + (size_t)2 * d * es;
@@ -404,19 +416,24 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
         hipError_t err = e->bf16 ? launch_attention_bf16(a, ls) : launch_attention_f32(a, ls);
         if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
       }
-      if ((rc = run_linear(e, ls, KC_OUT, u, d, w.wo, w.bo, x, d, Mg, d, d, EPI_BIAS_RESID))) return rc;
+      {
+        GemmArgs a{};
+        a.A = u; a.W = w.wo; a.bias = w.bo; a.out = x; a.M = Mg; a.N = d; a.K = d; a.lda = d; a.ldo = d;
+        a.w_panels = panels;
+        if ((rc = run_gemm(e, ls, KC_OUT, a, A_PLAIN, EPI_BIAS_RESID, d, 4, Mg, d))) return rc;
+      }
       if ((rc = run_ln(e, ls, KC_LN, x, w.ln2_g, w.ln2_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
       {   // fc1 writes the hidden activations as [rows/256][f/64][256][64] panels: one contiguous 32 KB block per
           // K step of fc2's activation operand (whose rows would otherwise be 2 f bytes apart in memory)
         GemmArgs a{};
         a.A = u; a.W = w.w1; a.bias = w.b1; a.out = hbuf; a.M = Mg; a.N = f; a.K = d; a.lda = d; a.ldo = f;
-        a.out_panels = panels;
+        a.out_panels = panels; a.w_panels = panels;
         if ((rc = run_gemm(e, ls, KC_FC1, a, A_PLAIN, EPI_BIAS_GELU, d, (int)es, Mg, d))) return rc;
       }
       {
         GemmArgs a{};
         a.A = hbuf; a.W = w.w2; a.bias = w.b2; a.out = x; a.M = Mg; a.N = d; a.K = f; a.lda = f; a.ldo = d;
-        a.a_panels = panels;
+        a.a_panels = panels; a.w_panels = panels;
         if ((rc = run_gemm(e, ls, KC_FC2, a, A_PLAIN, EPI_BIAS_RESID, f, 4, Mg, f))) return rc;
       }
     }

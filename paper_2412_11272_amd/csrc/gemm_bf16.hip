@@ -275,7 +275,9 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   for (int i = 0; i < WL; ++i) {
     const int rt = (i * NW + wave) * 8 + lrow;
     const int lch = (lane & 7) ^ ((rt >> 1) & 7);
-    wptr[i] = W + (size_t)(n0 + rt) * p.K + lch * 8;
+    const int n = n0 + rt;
+    wptr[i] = p.w_panels ? W + ((size_t)(n >> 8) * (p.K >> 6) << 14) + ((n & 255) << 6) + lch * 8
+                         : W + (size_t)n * p.K + lch * 8;
   }
 
   auto issue = [&](int kt) {
@@ -286,9 +288,10 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     for (int i = 0; i < XL; ++i)
       __builtin_amdgcn_global_load_lds((const glb_void *)(xptr[i] + ka),
                                        (lds_void *)(sX + stage * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+    const int kw = p.w_panels ? kt << 14 : k0;
 #pragma unroll
     for (int i = 0; i < WL; ++i)
-      __builtin_amdgcn_global_load_lds((const glb_void *)(wptr[i] + k0),
+      __builtin_amdgcn_global_load_lds((const glb_void *)(wptr[i] + kw),
                                        (lds_void *)(sW + stage * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
   };
 

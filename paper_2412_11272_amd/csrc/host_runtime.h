@@ -106,6 +106,23 @@ inline int upload_w(DevCtx *e, void **dst, const float *src, size_t n) {
 }
 inline int upload_w(DevCtx *e, void **dst, const std::vector<float> &src) { return upload_w(e, dst, src.data(), src.size()); }
 
+// Upload a weight matrix W [n_out, k] (k a multiple of 64) in panel layout [ceil(n_out/256)][k/64][256][64]
+// (rows beyond n_out zero): every K step of a GEMM tile then reads one contiguous block.  bf16 objects only.
+inline int upload_w_panels(DevCtx *e, void **dst, const float *src, int n_out, int k) {
+  const int np = (n_out + 255) / 256, kc = k / 64;
+  std::vector<uint16_t> tmp((size_t)np * kc * 16384, 0);
+  for (int n = 0; n < n_out; ++n)
+    for (int c = 0; c < kc; ++c) {
+      uint16_t *d = tmp.data() + (((size_t)(n >> 8) * kc + c) << 14) + ((n & 255) << 6);
+      const float *s = src + (size_t)n * k + c * 64;
+      for (int j = 0; j < 64; ++j) d[j] = f32_to_bf16_rne(s[j]);
+    }
+  int rc = dev_alloc(e, dst, tmp.size() * 2);
+  if (rc) return rc;
+  WF_HIP_TRY(hipMemcpy(*dst, tmp.data(), tmp.size() * 2, hipMemcpyHostToDevice));
+  return WF_OK;
+}
+
 inline int staging_create(DevCtx *e, size_t ints) {
   for (int i = 0; i < kStagingSlots; ++i) {
     WF_HIP_TRY(hipHostMalloc((void **)&e->stage_host[i], ints * 4, hipHostMallocDefault));

@@ -38,8 +38,9 @@ struct GemmArgs {
   int32_t group_n;          // tiles walk column groups of this many tile columns (>= tiles per row: plain row-major)
   // Panel layout (direct-load GEMM only): instead of row-major, a matrix is stored as [rows/256][cols/64][256][64],
   // i.e. every (256-row panel, 64-column chunk) is one contiguous 32 KB block -- exactly one K step of a
-  // tile's activation operand.  a_panels: A is read in that layout; out_panels: a bf16 result is written in it.
-  int32_t a_panels, out_panels;
+  // tile's operand.  a_panels: A is read in that layout; w_panels: W is (rows = output features, padded to a
+  // multiple of 256); out_panels: a bf16 result is written in it.
+  int32_t a_panels, w_panels, out_panels;
   // A_CONV3 only
   const int32_t *row_src;
   const int32_t *row_flags;
