@@ -48,10 +48,19 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   __shared__ __attribute__((aligned(1024))) unsigned char sK[2][BKV * 128];
   __shared__ __attribute__((aligned(1024))) unsigned char sV[2][BKV * 128];
 
-  const int item = blockIdx.x / p.n_heads;
-  const int head = blockIdx.x % p.n_heads;
+  // The grid has the head count rounded up to a multiple of 8.  Consecutive workgroups go to the 8 XCDs in
+  // turn, so slot s of every work item lands on XCD s % 8; slot s holds head (s - rot) mod heads8, with rot
+  // fixed per stream: every query block of one (stream, head) then finds its K and V in the same L2.  rot
+  // advances by n_heads % 8 from one stream to the next in the (cost-sorted) work list, so the XCDs that get
+  // one head more than the others change from stream to stream.  Slots without a head leave at once.
+  const int heads8 = (p.n_heads + 7) & ~7;
+  const int item = blockIdx.x / heads8;
+  const int w1 = p.work[2 * item + 1];
+  const int rot = (((w1 >> 20) & 7) * (p.n_heads & 7)) & 7;
+  const int head = (blockIdx.x % heads8 + heads8 - rot) % heads8;
+  if (head >= p.n_heads) return;
   const int stream = p.work[2 * item];
-  const int q0 = p.work[2 * item + 1];
+  const int q0 = w1 & 0xFFFFF;
   const int tok0 = p.cu_q[stream];
   const int Lq = p.cu_q[stream + 1] - tok0;
   const int ktok0 = p.cu_kv[stream];
@@ -235,11 +244,12 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.d_model != a.n_heads * 64) return hipErrorInvalidValue;
   if (a.ldq % 8 != 0 || a.ldkv % 8 != 0 || !a.q || !a.k || !a.v || !a.cu_q || !a.cu_kv) return hipErrorInvalidValue;
+  const dim3 grid(a.n_work * ((a.n_heads + 7) & ~7));
   if (a.causal) {
     if (a.cu_q != a.cu_kv) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attention_bf16_kernel<true>, dim3(a.n_work * a.n_heads), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(attention_bf16_kernel<true>, grid, dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL(attention_bf16_kernel<false>, dim3(a.n_work * a.n_heads), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(attention_bf16_kernel<false>, grid, dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }

@@ -55,7 +55,7 @@ int check_dec_config(const wf_decoder_config *c) {
   if (c->d_mlp < 128 || c->d_mlp % 128) return fail(WF_E_INVALID_ARG, "d_mlp = %d must be a positive multiple of 128", c->d_mlp);
   if (c->n_layers < 0) return fail(WF_E_INVALID_ARG, "n_layers = %d", c->n_layers);
   if (c->n_vocab < 1) return fail(WF_E_INVALID_ARG, "n_vocab = %d", c->n_vocab);
-  if (c->n_ctx < 1) return fail(WF_E_INVALID_ARG, "n_ctx = %d", c->n_ctx);
+  if (c->n_ctx < 1 || c->n_ctx > (1 << 20)) return fail(WF_E_INVALID_ARG, "n_ctx = %d (supported: 1 .. %d)", c->n_ctx, 1 << 20);
   if (c->max_streams < 1) return fail(WF_E_INVALID_ARG, "max_streams = %d", c->max_streams);
   if (c->max_enc_tokens < 1) return fail(WF_E_INVALID_ARG, "max_enc_tokens = %d", c->max_enc_tokens);
   if (c->max_prompt_tokens < 1) return fail(WF_E_INVALID_ARG, "max_prompt_tokens = %d", c->max_prompt_tokens);

@@ -124,6 +124,8 @@ int check_config(const wf_config *c) {
   if (c->max_streams < 1) return fail(WF_E_INVALID_ARG, "max_streams = %d", c->max_streams);
   if (c->max_frames_per_stream < 1 + c->hush_frames)
     return fail(WF_E_INVALID_ARG, "max_frames_per_stream = %d cannot hold one frame plus the hush segment", c->max_frames_per_stream);
+  if (c->max_frames_per_stream > (1 << 21) - 2)     // the attention work list keeps a query offset in 20 bits
+    return fail(WF_E_INVALID_ARG, "max_frames_per_stream = %d exceeds the supported %d", c->max_frames_per_stream, (1 << 21) - 2);
   if (c->max_total_frames < c->max_frames_per_stream)
     return fail(WF_E_INVALID_ARG, "max_total_frames = %d < max_frames_per_stream = %d", c->max_total_frames, c->max_frames_per_stream);
   if (c->precision != WF_PRECISION_BF16 && c->precision != WF_PRECISION_F32)

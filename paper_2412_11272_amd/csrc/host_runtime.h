@@ -244,14 +244,15 @@ inline int build_work(const int32_t *cu_q, int B, int q_tile, int32_t *work, con
   for (int i = 0; i < B; ++i) order[i] = {cost ? cost[i] : (int64_t)(cu_q[i + 1] - cu_q[i]), i};
   std::stable_sort(order.begin(), order.end(),
                    [](const std::pair<int64_t, int> &a, const std::pair<int64_t, int> &b) { return a.first > b.first; });
-  int n = 0;
+  int n = 0, rank = 0;
   for (const auto &o : order) {
     const int Lq = cu_q[o.second + 1] - cu_q[o.second];
     for (int q0 = 0; q0 < Lq; q0 += q_tile) {
       work[2 * n] = o.second + stream_base;     // cu_q points at the first of the B streams; ids stay absolute
-      work[2 * n + 1] = q0;
+      work[2 * n + 1] = q0 | ((rank & 7) << 20); // the stream's rank mod 8 rides along (head -> XCD rotation)
       ++n;
     }
+    ++rank;
   }
   return n;
 }
