@@ -239,7 +239,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
 
 // One BM x BN output tile at (m0, n0), computed by the whole workgroup.
-template <int BM, int BN, int WM, int WN, int EPI, int SMEM>   // SMEM: bytes of LDS the kernel owns
+template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT>   // SMEM: bytes of LDS the kernel owns; NT: streaming stores
 __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -442,7 +442,11 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
         const int n = nw0 + c * 8;
         __bf16 *dst = p.out_panels ? (__bf16 *)p.out + ((((size_t)(m >> 8) * (p.N >> 6) + (n >> 6)) << 14) + ((m & 255) << 6) + (n & 63))
                                    : (__bf16 *)p.out + (size_t)m * p.ldo + n;
-        *(u32x4 *)dst = v;
+        // Large bf16 results (QKV, the MLP's hidden activations) are written with the non-temporal hint:
+        // they are far bigger than what the caches can hand to the consumer, and written plainly they
+        // push the residual stream and the operands of the next kernels out of the memory-side cache.
+        if constexpr (NT) __builtin_nontemporal_store(v, (u32x4 *)dst);
+        else *(u32x4 *)dst = v;
       }
     }
   } else {
@@ -515,7 +519,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 // them is split into two BM x BN/2 units so that the last round takes half as long (620 tiles on 256 CUs:
 // 2.5 rounds instead of 3).  Consecutive workgroup ids go to different XCDs; XCD x gets the full tiles at
 // positions [x*full_per_xcd, ...) of the order and the half units [x*half_per_xcd, ...), full tiles first.
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tiles_n = p.N / BN, tiles_m = (p.M + BM - 1) / BM;
@@ -535,20 +539,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
     const int tile = xcd * p.full_per_xcd + l;
     if (tile >= p.n_full) return;
     locate(tile, row, col);
-    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128>(p, smem, row * BM, col * BN);
+    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128, NT>(p, smem, row * BM, col * BN);
   } else {
     const int hl = l - p.full_per_xcd;
     const int h = xcd * p.half_per_xcd + hl;
     if (hl >= p.half_per_xcd || h >= p.n_half) return;
     locate(p.n_full + (h >> 1), row, col);
-    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
+    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128, NT>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT = false>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -584,10 +588,14 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
     if (a.out_panels && epi != EPI_BIAS && epi != EPI_BIAS_GELU) return hipErrorInvalidValue;   // bf16 results only
+    // streaming stores for bf16 results no cache level could hand on whole (threshold: twice the 32 MB of L2)
+    const bool nt = big && (size_t)a.M * a.N * 2 >= ((size_t)64 << 20);
     switch (epi) {
       case EPI_BIAS:
+        if (nt) return launch_dl<256, 256, 4, 2, EPI_BIAS, true>(a, s);
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS>(a, s);
       case EPI_BIAS_GELU:
+        if (nt) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU, true>(a, s);
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU>(a, s);
       case EPI_BIAS_RESID:
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_RESID>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_RESID>(a, s);
