@@ -239,7 +239,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
 
 // One BM x BN output tile at (m0, n0), computed by the whole workgroup.
-template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT>   // SMEM: bytes of LDS the kernel owns; NT: streaming stores
+// Zero source for the masked taps of the convolution operand (device code takes its address directly).
+__device__ __attribute__((aligned(16))) unsigned int g_zero16[4];
+
+template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT, int AMODE>   // SMEM: bytes of LDS the kernel owns; NT: streaming stores
 __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -262,14 +265,21 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   const __bf16 *W = (const __bf16 *)p.W;
   const __bf16 *xptr[XL];
   const __bf16 *wptr[WL];
+  [[maybe_unused]] int xflags[XL];      // A_CONV3: bit 0 = first tap lies before the stream, bit 1 = last tap lies after it
 #pragma unroll
   for (int i = 0; i < XL; ++i) {
     const int rt = (i * NW + wave) * 8 + lrow;
     const int lch = (lane & 7) ^ ((rt >> 1) & 7);
     int row = m0 + rt;
     row = row < p.M ? row : p.M - 1;              // rows past M are computed but never stored
-    xptr[i] = p.a_panels ? A + ((size_t)(row >> 8) * (p.K >> 6) << 14) + ((row & 255) << 6) + lch * 8   // panel layout
-                         : A + (size_t)row * p.lda + lch * 8;
+    if constexpr (AMODE == A_CONV3) {
+      // row = window of 3*C elements starting at frame row_src[row]; C % 64 == 0, so a K step lies in one tap
+      xptr[i] = A + (long)p.row_src[row] * p.C + lch * 8;
+      xflags[i] = p.row_flags[row];
+    } else {
+      xptr[i] = p.a_panels ? A + ((size_t)(row >> 8) * (p.K >> 6) << 14) + ((row & 255) << 6) + lch * 8   // panel layout
+                           : A + (size_t)row * p.lda + lch * 8;
+    }
   }
 #pragma unroll
   for (int i = 0; i < WL; ++i) {
@@ -280,14 +290,20 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
                          : W + (size_t)n * p.K + lch * 8;
   }
 
+  [[maybe_unused]] const int kpt = AMODE == A_CONV3 ? p.C / BK : 0;     // K steps per tap
   auto issue = [&](int kt) {
     const int stage = kt & 1;
     const int k0 = kt * BK;
     const int ka = p.a_panels ? kt << 14 : k0;     // panel layout: the next 64-column chunk is 256 * 64 elements on
+    // A_CONV3: K steps [0, kpt) are tap 0, [2 kpt, 3 kpt) tap 2; the flag bit that zeroes this step's tap
+    const int dead = AMODE == A_CONV3 ? (kt < kpt ? 1 : (kt >= 2 * kpt ? 2 : 0)) : 0;
 #pragma unroll
-    for (int i = 0; i < XL; ++i)
-      __builtin_amdgcn_global_load_lds((const glb_void *)(xptr[i] + ka),
+    for (int i = 0; i < XL; ++i) {
+      const __bf16 *src = xptr[i] + ka;
+      if constexpr (AMODE == A_CONV3) src = (xflags[i] & dead) ? (const __bf16 *)g_zero16 : src;
+      __builtin_amdgcn_global_load_lds((const glb_void *)src,
                                        (lds_void *)(sX + stage * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+    }
     const int kw = p.w_panels ? kt << 14 : k0;
 #pragma unroll
     for (int i = 0; i < WL; ++i)
@@ -450,7 +466,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       }
     }
   } else {
-    // fp32 output: residual update in place (EPI_BIAS_RESID) or plain store (EPI_BIAS_F32), PW features
+    // fp32 output: residual update in place (EPI_BIAS_RESID), GELU plus position row (EPI_BIAS_GELU_POS) or
+    // plain store (EPI_BIAS_F32), PW features
     // (PW * 4 bytes per row) per pass
     constexpr int PW = TN >= 64 ? 64 : TN;         // features per pass
     constexpr int RB = PW * 4, CPR = RB / 16, RPI = 64 / CPR;
@@ -464,9 +481,13 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     auto fetch_res = [&](int ps, int it) {
       int m = mw0 + it * RPI + rr;
       m = m < p.M ? m : p.M - 1;
-      res[ps & 1][it] = *(const f32x4 *)((const float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
+      if constexpr (EPI == EPI_BIAS_GELU_POS)      // the addend is the token's position row instead of the old output
+        res[ps & 1][it] = *(const f32x4 *)(p.pos + (size_t)p.row_pos[m] * p.N + nw0 + ps * PW + c * 4);
+      else
+        res[ps & 1][it] = *(const f32x4 *)((const float *)p.out + (size_t)m * p.ldo + nw0 + ps * PW + c * 4);
     };
-    if (EPI == EPI_BIAS_RESID) {
+    constexpr bool ADDEND = EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU_POS;
+    if (ADDEND) {
 #pragma unroll
       for (int it = 0; it < NIT / 2; ++it) fetch_res(0, it);
     }
@@ -482,12 +503,12 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
           const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
           f32x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e] + b[e];
+          for (int e = 0; e < 4; ++e) v[e] = EPI == EPI_BIAS_GELU_POS ? gelu_fast(acc[i][j][e] + b[e]) : acc[i][j][e] + b[e];
           const int ch = (nl % PW) >> 2;           // 16-byte chunk inside the pass
           *(f32x4 *)(stg + r * RB + ((ch ^ (r & (CPR - 1))) << 4)) = v;
         }
       }
-      if (EPI == EPI_BIAS_RESID) {
+      if (ADDEND) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int it = NIT / 2; it < NIT; ++it) fetch_res(ps, it);
@@ -503,7 +524,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
         const int r = it * RPI + rr;
         f32x4 v = *(const f32x4 *)(stg + r * RB + ((c ^ (r & (CPR - 1))) << 4));
         const int m = mw0 + r;
-        if (EPI == EPI_BIAS_RESID) {
+        if (ADDEND) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] += res[ps & 1][it][e];
         }
@@ -519,7 +540,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 // them is split into two BM x BN/2 units so that the last round takes half as long (620 tiles on 256 CUs:
 // 2.5 rounds instead of 3).  Consecutive workgroup ids go to different XCDs; XCD x gets the full tiles at
 // positions [x*full_per_xcd, ...) of the order and the half units [x*half_per_xcd, ...), full tiles first.
-template <int BM, int BN, int WM, int WN, int EPI, bool NT>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT, int AMODE>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tiles_n = p.N / BN, tiles_m = (p.M + BM - 1) / BM;
@@ -539,20 +560,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
     const int tile = xcd * p.full_per_xcd + l;
     if (tile >= p.n_full) return;
     locate(tile, row, col);
-    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128, NT>(p, smem, row * BM, col * BN);
+    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128, NT, AMODE>(p, smem, row * BM, col * BN);
   } else {
     const int hl = l - p.full_per_xcd;
     const int h = xcd * p.half_per_xcd + hl;
     if (hl >= p.half_per_xcd || h >= p.n_half) return;
     locate(p.n_full + (h >> 1), row, col);
-    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128, NT>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
+    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128, NT, AMODE>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool NT = false>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = A_PLAIN>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT, AMODE>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -605,11 +626,16 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
     }
   }
   if (a.C % 8 != 0 || 3 * a.C > a.K || !a.row_src || !a.row_flags) return hipErrorInvalidValue;
+  // Taps that are whole K steps (C a multiple of 64, no padding after the third tap) go through the
+  // direct-load kernel: a masked tap is then a whole 16-byte load redirected to a zero source.
+  const bool direct = big && a.C % BK == 0 && 3 * a.C == a.K && !a.a_panels && !a.w_panels && !a.out_panels;
   switch (epi) {
     case EPI_BIAS_GELU:
+      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU, false, A_CONV3>(a, s);
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU>(a, s) : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU>(a, s);
     case EPI_BIAS_GELU_POS:
       if (!a.pos || !a.row_pos) return hipErrorInvalidValue;
+      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU_POS, false, A_CONV3>(a, s);
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s)
                  : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;

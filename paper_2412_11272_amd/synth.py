@@ -47,6 +47,9 @@ SHAPES: Dict[str, Shape] = {
     "large-v3": Shape(128, 1280, 32, 20, 5120),
     # not one of the five benchmark shapes: a two-layer, two-head shape for fast unit tests
     "unit": Shape(16, 128, 2, 2, 256),
+    # stem only (no transformer block): lets a test drive the two convolutions at a batch size that takes
+    # their large-tile kernels while the oracle still finishes in seconds
+    "stem": Shape(128, 256, 0, 4, 1024),
 }
 
 
@@ -329,6 +332,9 @@ def workload(name: str) -> Workload:
         return Workload(name, S["tiny"], [100, 333, 41, 1, 702, 256], seed_index=8)
     if name == "tiny-sharp":
         return Workload(name, S["tiny"], [100, 333, 41, 1, 702, 256], seed_index=8, q_scale=8.0)
+    if name == "stem-wide":
+        # 36 long streams (odd and even lengths, one short, one single frame): ~53 k tokens
+        return Workload(name, S["stem"], [2901 + 7 * (i % 5) for i in range(34)] + [77, 1], seed_index=9)
     raise KeyError(name)
 
 

@@ -24,6 +24,14 @@ def _check(name, precision, affine=False, **kw):
     return err, worst
 
 
+def test_stem_alone_at_large_tile_batch_size():
+    """No transformer block, ~53 k tokens: both convolutions take the 256 x 256 direct-load kernel (gathered
+    3-tap windows, taps masked at every stream boundary, GELU + position epilogue); whole output against the
+    oracle."""
+    err, worst = _check("stem-wide", wf.WF_PRECISION_BF16, affine=True)
+    assert err <= 2e-2 and worst <= 2e-2, (err, worst)
+
+
 @pytest.mark.parametrize("name,affine", [("unit", True), ("unit-sharp", True), ("tiny-ragged", False), ("tiny-sharp", True),
                                          ("cfg1", False), ("cfg2-2s", False), ("cfg2-4s", False), ("cfg2-8s", False),
                                          ("cfg3", False)])
