@@ -512,7 +512,8 @@ int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const
   if (!qkv_dev || !out_dev || !cu_seqlens_host) return fail(WF_E_INVALID_ARG, "NULL pointer");
   if (B < 1 || n_heads < 1 || cu_seqlens_host[0] != 0) return fail(WF_E_INVALID_ARG, "need B >= 1, n_heads >= 1, cu_seqlens[0] == 0");
   for (int i = 0; i < B; ++i)
-    if (cu_seqlens_host[i + 1] <= cu_seqlens_host[i]) return fail(WF_E_INVALID_ARG, "stream %d is empty", i);
+    if (cu_seqlens_host[i + 1] <= cu_seqlens_host[i] || cu_seqlens_host[i + 1] - cu_seqlens_host[i] > (1 << 20))
+      return fail(WF_E_INVALID_ARG, "stream %d: need 1 .. %d tokens", i, 1 << 20);
   const int M = cu_seqlens_host[B];
   const int qt = attention_q_tile();
   std::vector<int32_t> idx((size_t)(B + 1) + 2 * ((size_t)M / qt + B + 1));
