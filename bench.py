@@ -80,16 +80,20 @@ def bench_frontend(wl, n_frames, steps, warmup):
     for _ in range(warmup):
         fe.logmel(audio, offs, lens, out=out)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(steps):
+    # one event pair per call and the median over calls: the HIP runtime stalls the host once for tens of
+    # milliseconds after a few dozen back-to-back sub-millisecond calls, which says nothing about the kernels
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record()
         fe.logmel(audio, offs, lens, out=out)
-    e1.record()
+        e1.record()
     torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / steps
+    per_call = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    ms = per_call[len(per_call) // 2]
+    ms_mean = sum(per_call) / len(per_call)
     fe.close()
     flops = frames * (2.0 * 2 * 400 * 201)                     # the DFT contraction; the mel filters are a few % of it
-    return {"ms": round(ms, 4), "frames": int(frames), "audio_s_per_s": round(sum(lens) / 16000.0 / (ms / 1e3), 1),
+    return {"ms": round(ms, 4), "ms_mean": round(ms_mean, 4), "timing": "median of per-call HIP-event times", "frames": int(frames), "audio_s_per_s": round(sum(lens) / 16000.0 / (ms / 1e3), 1),
             "dft_tflops": round(flops / ms / 1e9, 2), "peak_fp32_mfma_tflops": 157.3,
             "frac": round(flops / ms / 1e9 / 157.3, 4), "dtype": "f32"}
 
