@@ -259,6 +259,7 @@ def main():
     enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)
     if args.lanes > 0:
         enc.set_lanes(args.lanes)
+    lanes_timed = enc.get_lanes()
     flat, offs, nf = wf.pack_mels(mels)
     mel = torch.from_numpy(flat).cuda()
     cu, total_frames, M = wf.plan_batch(enc.cfg, nf)
@@ -285,8 +286,8 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
 
-    # same steps again with every launch bracketed by HIP events on the launch stream, on ONE lane (the
-    # default) so that a kernel's duration is its own: with --lanes > 1 kernels of different groups overlap
+    # same steps again with every launch bracketed by HIP events on the launch stream, on ONE lane so that a
+    # kernel's duration is its own: with more lanes kernels of different groups overlap
     enc.set_lanes(1)
     enc.set_profiling(True)
     torch.cuda.synchronize()
@@ -335,7 +336,7 @@ def main():
         "config": {"workload": f"{wl.name}: large-v3-shaped encoder, 64 ragged streams" if wl.name == "cfg5" else wl.name,
                    "streams": len(nf), "tokens": int(M), "frames_incl_hush": int(total_frames),
                    "payload_audio_s": payload_audio_s, "d_model": wl.shape.d_model, "n_layers": wl.shape.n_layers,
-                   "lanes": args.lanes if args.lanes > 0 else 1},
+                   "lanes": lanes_timed},
         "tokens_per_s": round(M / dt, 1),
         "audio_s_per_s_incl_hush": round(total_frames / synth.FRAMES_PER_SECOND / dt, 1),
         "algorithmic_tflops": round(flops / dt / 1e12, 1),

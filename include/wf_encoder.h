@@ -158,11 +158,14 @@ typedef struct {
 int wf_kernel_class_count(void);
 int wf_encoder_set_profiling(wf_encoder *enc, int32_t enabled);
 int wf_encoder_kernel_stats(wf_encoder *enc, wf_kernel_stat *stats, int32_t n_stats);
-/* Number of lanes (1 .. 4, default 1): a batch of at least 4096 tokens per lane is cut into that many
+/* Number of lanes (1 .. 4, default 2): a batch of at least 4096 tokens per lane is cut into that many
  * contiguous groups of streams which run the layer sequence on streams of their own (lane 0 on the caller's),
- * so that one group's bandwidth-bound kernels and GEMM tails overlap another group's matrix work (worth at most
- * 1-2 % on a power-limited part).  Results do not depend on it.  The call is still ordered on hip_stream as a whole. */
+ * so that one group's bandwidth-bound kernels and GEMM tails overlap another group's matrix work (worth 1-2 %
+ * on a power-limited part).  Results do not depend on it.  The call is still ordered on hip_stream as a whole:
+ * the other lanes start after the work already queued on hip_stream and hip_stream waits for them before the
+ * call's work counts as done.  wf_encoder_get_lanes returns the current setting (negative WF_E_* on error). */
 int wf_encoder_set_lanes(wf_encoder *enc, int32_t n_lanes);
+int wf_encoder_get_lanes(const wf_encoder *enc);
 /* The configuration the encoder was created with (ln_eps as resolved). */
 int wf_encoder_get_config(const wf_encoder *enc, wf_config *cfg);
 

@@ -97,7 +97,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_frontend_create", "wf_logmel_batch", "wf_frontend_destroy",
            "wf_decoder_config_check", "wf_decoder_create", "wf_cross_kv", "wf_prefill", "wf_decoder_destroy",
            "wf_decoder_kernel_class_count", "wf_decoder_set_profiling", "wf_decoder_kernel_stats",
-           "wf_encoder_get_config", "wf_encoder_set_lanes", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
+           "wf_encoder_get_config", "wf_encoder_set_lanes", "wf_encoder_get_lanes", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy"]
@@ -145,6 +145,7 @@ def lib() -> C.CDLL:
     L.wf_decoder_kernel_stats.argtypes = [C.c_void_p, C.POINTER(WfKernelStat), C.c_int32]
     L.wf_encoder_get_config.argtypes = [C.c_void_p, C.POINTER(WfConfig)]
     L.wf_encoder_set_lanes.argtypes = [C.c_void_p, C.c_int32]
+    L.wf_encoder_get_lanes.argtypes = [C.c_void_p]
     _lp = C.POINTER(C.c_int64)
     L.wf_rounds_create.argtypes = [C.POINTER(WfRoundsConfig), _lp, C.POINTER(C.c_void_p)]
     L.wf_rounds_begin.argtypes = [C.c_void_p, _lp, _ip, _ip]
@@ -246,6 +247,11 @@ class Encoder:
 
     def set_lanes(self, n: int):
         _check(lib().wf_encoder_set_lanes(self._h, int(n)))
+
+    def get_lanes(self) -> int:
+        n = lib().wf_encoder_get_lanes(self._h)
+        _check(min(n, 0))
+        return n
 
     def kernel_stats(self) -> List[dict]:
         n = lib().wf_kernel_class_count()

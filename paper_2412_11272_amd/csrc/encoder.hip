@@ -48,10 +48,10 @@ constexpr int kMaxLanes = 4;
 
 struct wf_encoder : DevCtx {
   wf_config cfg{};
-  // Lanes (optional, wf_encoder_set_lanes): the batch is cut into contiguous groups of streams that run the
+  // Lanes (wf_encoder_set_lanes): the batch is cut into contiguous groups of streams that run the
   // whole layer sequence on streams of their own, so that one group's bandwidth-bound kernels and GEMM tails
   // overlap the other's matrix work.  Lane 0 is the caller's stream.
-  int n_lanes = 1;
+  int n_lanes = 2;
   hipStream_t lane_stream[kMaxLanes] = {};
   hipEvent_t lane_done[kMaxLanes] = {};
   hipEvent_t fork_evt = nullptr;
@@ -464,6 +464,11 @@ int wf_encoder_set_lanes(wf_encoder *e, int32_t n_lanes) {
   if (n_lanes < 1 || n_lanes > kMaxLanes) return fail(WF_E_INVALID_ARG, "n_lanes = %d, need 1 .. %d", n_lanes, (int)kMaxLanes);
   e->n_lanes = n_lanes;
   return WF_OK;
+}
+
+int wf_encoder_get_lanes(const wf_encoder *e) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  return e->n_lanes;
 }
 
 int wf_encoder_get_config(const wf_encoder *e, wf_config *cfg) {
