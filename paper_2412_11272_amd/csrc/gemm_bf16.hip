@@ -1,16 +1,18 @@
 // bf16 MFMA GEMMs for gfx950:  out = epilogue(A . W^T),  A [M, K] activations, W [N, K] weights, fp32
-// accumulation, built from v_mfma_f32_32x32x16_bf16.  Two kernels share the tiling:
+// accumulation.  Two kernels share the tiling:
 //
-//   gemm_bf16_dl_kernel   the projections of a transformer block (QKV, out, fc1, fc2).  Operand tiles go
-//                         global -> LDS directly (global_load_lds_dwordx4), fragments are double-buffered
-//                         in registers, the epilogue is transposed through LDS so that stores cover whole
-//                         row segments.
-//   gemm_bf16_kernel      the two convolutions of the stem: a width-3 convolution over a packed time-major
-//                         matrix is a GEMM whose A row is the contiguous window of three frames, with the
-//                         first / last tap zeroed at stream boundaries.  The masking needs the operand in
-//                         registers, so tiles go global -> registers -> LDS.
+//   gemm_bf16_dl_kernel   (v_mfma_f32_16x16x32_bf16) the projections of a transformer block (QKV, out, fc1,
+//                         fc2) and, when a tap is a whole number of K steps, the two convolutions of the
+//                         stem.  Operand tiles go global -> LDS directly (global_load_lds_dwordx4),
+//                         fragments are double-buffered in registers, the epilogue is transposed through
+//                         LDS so that stores cover whole row segments.
+//   gemm_bf16_kernel      (v_mfma_f32_32x32x16_bf16) the remaining convolution shapes: a width-3 convolution
+//                         over a packed time-major matrix is a GEMM whose A row is the contiguous window
+//                         of three frames, with the first / last tap zeroed at stream boundaries.  Here
+//                         the masking is done in registers, so tiles go global -> registers -> LDS.
 //
-// Tiling: one workgroup computes a BM x BN tile and advances K by 64 through two LDS stages; each wave
+// Tiling: one workgroup computes a BM x BN tile and advances K by 64 through two LDS stages per operand
+// (three for the activations of the row-major residual projections, which then run two steps ahead); each wave
 // owns a (BM/WM) x (BN/WN) sub-tile.  The weight fragment is the MFMA's first operand and the activation
 // fragment the second, so a lane ends up holding four consecutive output features of one token.
 // LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row >> 1) & 7.  The LDS
@@ -238,11 +240,13 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
 
-// One BM x BN output tile at (m0, n0), computed by the whole workgroup.
 // Zero source for the masked taps of the convolution operand (device code takes its address directly).
 __device__ __attribute__((aligned(16))) unsigned int g_zero16[4];
 
-template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT, int AMODE>   // SMEM: bytes of LDS the kernel owns; NT: streaming stores
+// One BM x BN output tile at (m0, n0), computed by the whole workgroup.  SMEM: bytes of LDS the kernel owns;
+// NT: streaming stores for bf16 results; AMODE: plain or gathered convolution operand; DEEP: which operand
+// gets a third LDS stage and a prefetch distance of two K steps (0 none, 1 activations, 2 weights).
+template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT, int AMODE, int DEEP>
 __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -250,8 +254,9 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   constexpr int WL = BN / 8 / NW;
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TN % 32 == 0, "tile/waves mismatch");
 
-  unsigned char *sX = smem;                        // [2][BM][128 B]
-  unsigned char *sW = smem + 2 * BM * 128;         // [2][BN][128 B]
+  constexpr int XS = DEEP == 1 ? 3 : 2, WS = DEEP == 2 ? 3 : 2;   // LDS stages per operand
+  unsigned char *sX = smem;                        // [XS][BM][128 B]
+  unsigned char *sW = smem + XS * BM * 128;        // [WS][BN][128 B]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -291,8 +296,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   }
 
   [[maybe_unused]] const int kpt = AMODE == A_CONV3 ? p.C / BK : 0;     // K steps per tap
-  auto issue = [&](int kt) {
-    const int stage = kt & 1;
+  auto issue_x = [&](int kt, int slot) {            // activation tile of K step kt into ring slot `slot` (= kt % 3)
     const int k0 = kt * BK;
     const int ka = p.a_panels ? kt << 14 : k0;     // panel layout: the next 64-column chunk is 256 * 64 elements on
     // A_CONV3: K steps [0, kpt) are tap 0, [2 kpt, 3 kpt) tap 2; the flag bit that zeroes this step's tap
@@ -302,13 +306,15 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       const __bf16 *src = xptr[i] + ka;
       if constexpr (AMODE == A_CONV3) src = (xflags[i] & dead) ? (const __bf16 *)g_zero16 : src;
       __builtin_amdgcn_global_load_lds((const glb_void *)src,
-                                       (lds_void *)(sX + stage * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+                                       (lds_void *)(sX + slot * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
     }
-    const int kw = p.w_panels ? kt << 14 : k0;
+  };
+  auto issue_w = [&](int kt, int slot) {
+    const int kw = p.w_panels ? kt << 14 : kt * BK;
 #pragma unroll
     for (int i = 0; i < WL; ++i)
       __builtin_amdgcn_global_load_lds((const glb_void *)(wptr[i] + kw),
-                                       (lds_void *)(sW + stage * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
+                                       (lds_void *)(sW + slot * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
   };
 
   // Accumulators: v_mfma_f32_16x16x32_bf16 blocks, TB token blocks x FB feature blocks of 16 x 16.  With
@@ -344,13 +350,13 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   // held up handing loads to the memory pipeline.
   const bool early = (wave < NW / 2) || NW < 8;
   bf16x8 xf[2][TB], wlo[FBH], whi[FBH];
-  auto rd_x = [&](int stage, int t, int buf) {
-    const unsigned char *cx = sX + stage * BM * 128 + xrow0 + (((4 * t + lq) ^ sw) << 4);
+  auto rd_x = [&](int slot, int t, int buf) {
+    const unsigned char *cx = sX + slot * BM * 128 + xrow0 + (((4 * t + lq) ^ sw) << 4);
 #pragma unroll
     for (int i = 0; i < TB; ++i) xf[buf][i] = *(const bf16x8 *)(cx + i * 16 * 128);
   };
-  auto rd_w = [&](int stage, int t, int half, bf16x8 (&dst)[FBH]) {
-    const unsigned char *cw = sW + stage * BN * 128 + wrow0 + half * FBH * 16 * 128 + (((4 * t + lq) ^ sw) << 4);
+  auto rd_w = [&](int slot, int t, int half, bf16x8 (&dst)[FBH]) {
+    const unsigned char *cw = sW + slot * BN * 128 + wrow0 + half * FBH * 16 * 128 + (((4 * t + lq) ^ sw) << 4);
 #pragma unroll
     for (int j = 0; j < FBH; ++j) dst[j] = *(const bf16x8 *)(cw + j * 16 * 128);
   };
@@ -371,48 +377,76 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   __builtin_amdgcn_sched_group_barrier(0x008, (TB * FBH > (NRD) ? TB * FBH - (NRD) : 0), 0);          \
   __builtin_amdgcn_sched_barrier(0)
 
-  issue(0);
+  // Operand pipeline.  Each operand has two LDS stages and is requested one K step ahead; with DEEP one of
+  // them has three stages and is requested two steps ahead (the activations of a row-major tile order come
+  // from further away than the weights, which stay in L2).  The deep operand is issued last: at the end of
+  // step kt a wave has then issued ... shallow(kt+1), deep(kt+2) as its newest loads, and since vector-memory
+  // operations complete in order, waiting until at most the loads of deep(kt+2) are outstanding means
+  // everything step kt+1 reads has landed.  Slots: stage kt % 2, or kt % 3 for the deep operand.
+  constexpr int NDEEP = DEEP == 1 ? XL : (DEEP == 2 ? WL : 0);       // load instructions of one deep tile
+  auto issue_next = [&](int kt, int s2, int s3) {    // after the barrier that ends step kt (s2 = kt % 2, s3 = kt % 3)
+    if (DEEP == 0) {
+      if (kt + 2 < nk) { issue_x(kt + 2, s2); issue_w(kt + 2, s2); }
+    } else if (DEEP == 1) {
+      if (kt + 2 < nk) issue_w(kt + 2, s2);
+      if (kt + 3 < nk) issue_x(kt + 3, s3);
+    } else {
+      if (kt + 2 < nk) issue_x(kt + 2, s2);
+      if (kt + 3 < nk) issue_w(kt + 3, s3);
+    }
+  };
+  issue_x(0, 0);
+  issue_w(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
   __builtin_amdgcn_s_barrier();
-  if (1 < nk) issue(1);
+  if (1 < nk) { issue_x(1, 1); issue_w(1, 1); }
+  if (DEEP == 1 && 2 < nk) issue_x(2, 2);
+  if (DEEP == 2 && 2 < nk) issue_w(2, 2);
   rd_x(0, 0, 0);
   rd_w(0, 0, 0, wlo);
+  int s3 = 0;                                      // kt % 3
   for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
+    const int s2 = kt & 1;
+    const int s3n = s3 == 2 ? 0 : s3 + 1;
+    const int xs = DEEP == 1 ? s3 : s2, xs1 = DEEP == 1 ? s3n : s2 ^ 1;     // activation slots of steps kt, kt+1
+    const int ws = DEEP == 2 ? s3 : s2, ws1 = DEEP == 2 ? s3n : s2 ^ 1;     // weight slots
     __builtin_amdgcn_sched_barrier(0);
     // (t = 0, lo): read the upper weight fragments of step 0
     __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0), placed BEFORE the next reads so it only waits for older ones
     __builtin_amdgcn_sched_barrier(0);
-    rd_w(st, 0, 1, whi);
+    rd_w(ws, 0, 1, whi);
     mm(0, wlo, 0);
     WF_SCHED(FBH);
     // (t = 0, hi): read the activation and lower weight fragments of step 1
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
-    rd_x(st, 1, 1);
-    rd_w(st, 1, 0, wlo);
+    rd_x(xs, 1, 1);
+    rd_w(ws, 1, 0, wlo);
     mm(1, whi, 0);
     WF_SCHED(TB + FBH);
     // (t = 1, lo): read the upper weight fragments of step 1
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
-    rd_w(st, 1, 1, whi);
+    rd_w(ws, 1, 1, whi);
     mm(0, wlo, 1);
     WF_SCHED(FBH);
-    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0): stage st fully read, my part of tile kt+1 landed
+    // this step's stages fully read; my part of the tiles of step kt+1 landed (deep(kt+2) may still be in flight)
+    if (DEEP != 0 && kt + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0070 | NDEEP);   // vmcnt(NDEEP) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);                                    // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 2 < nk && early) issue(kt + 2);
+    if (early) issue_next(kt, s2, s3);
     __builtin_amdgcn_sched_barrier(0);
     if (kt + 1 < nk) {
-      rd_x(st ^ 1, 0, 0);
-      rd_w(st ^ 1, 0, 0, wlo);
+      rd_x(xs1, 0, 0);
+      rd_w(ws1, 0, 0, wlo);
     }
     __builtin_amdgcn_sched_barrier(0);
     mm(1, whi, 1);                                 // (t = 1, hi)
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 2 < nk && !early) issue(kt + 2);
+    if (!early) issue_next(kt, s2, s3);
     __builtin_amdgcn_sched_barrier(0);
+    s3 = s3n;
   }
 #undef WF_SCHED
 
@@ -423,7 +457,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __builtin_amdgcn_s_barrier();                    // every wave is done reading the last K step
   unsigned char *stg = smem + wave * (TM * 256);   // TM rows x 256 bytes (<= 16 KB per wave)
-  static_assert(NW * TM * 256 <= SMEM && 2 * (BM + BN) * 128 <= SMEM, "staging does not fit in the LDS stages");
+  static_assert(NDEEP < 16 && NW * TM * 256 <= SMEM && (XS * BM + WS * BN) * 128 <= SMEM, "staging does not fit in the LDS stages");
   const int mw0 = m0 + wm * TM, nw0 = n0 + wn * TN;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
     constexpr int RB = TN * 2;                     // row bytes (bf16)
@@ -540,8 +574,9 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 // them is split into two BM x BN/2 units so that the last round takes half as long (620 tiles on 256 CUs:
 // 2.5 rounds instead of 3).  Consecutive workgroup ids go to different XCDs; XCD x gets the full tiles at
 // positions [x*full_per_xcd, ...) of the order and the half units [x*half_per_xcd, ...), full tiles first.
-template <int BM, int BN, int WM, int WN, int EPI, bool NT, int AMODE>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT, int AMODE, int DEEP>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
+  constexpr int SMEM = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tiles_n = p.N / BN, tiles_m = (p.M + BM - 1) / BM;
   // position t of the tile order -> (row, column): column groups of G tile columns, rows inside a group,
@@ -560,20 +595,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
     const int tile = xcd * p.full_per_xcd + l;
     if (tile >= p.n_full) return;
     locate(tile, row, col);
-    dl_tile<BM, BN, WM, WN, EPI, 2 * (BM + BN) * 128, NT, AMODE>(p, smem, row * BM, col * BN);
+    dl_tile<BM, BN, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, row * BM, col * BN);
   } else {
     const int hl = l - p.full_per_xcd;
     const int h = xcd * p.half_per_xcd + hl;
     if (hl >= p.half_per_xcd || h >= p.n_half) return;
     locate(p.n_full + (h >> 1), row, col);
-    dl_tile<BM, BN / 2, WM, WN, EPI, 2 * (BM + BN) * 128, NT, AMODE>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
+    dl_tile<BM, BN / 2, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = A_PLAIN>
+template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = A_PLAIN, int DEEP = 0>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
-  constexpr int smem = 2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT, AMODE>;
+  constexpr int smem = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT, AMODE, DEEP>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -619,7 +654,7 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
         if (nt) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU, true>(a, s);
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU>(a, s);
       case EPI_BIAS_RESID:
-        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_RESID>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_RESID>(a, s);
+        return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_RESID, false, A_PLAIN, 1>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_RESID>(a, s);
       case EPI_BIAS_F32:
         return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_F32>(a, s) : launch_dl<128, 128, 2, 2, EPI_BIAS_F32>(a, s);
       default: return hipErrorInvalidValue;
@@ -635,7 +670,7 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU>(a, s) : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU>(a, s);
     case EPI_BIAS_GELU_POS:
       if (!a.pos || !a.row_pos) return hipErrorInvalidValue;
-      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU_POS, false, A_CONV3>(a, s);
+      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU_POS, false, A_CONV3, 1>(a, s);
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s)
                  : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;
