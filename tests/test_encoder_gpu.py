@@ -182,3 +182,23 @@ def test_kernel_stats_cover_every_launch():
         assert sum(s["launches"] for s in enc.kernel_stats()) == 0
     finally:
         enc.close()
+
+def test_many_short_streams():
+    """400 streams of 1..40 frames (rows of the work list, index arrays and prefix sums far outnumber the
+    tiles): both precisions against the oracle."""
+    import torch
+    shape = synth.SHAPES["unit"]
+    rng = np.random.default_rng(400)
+    nf = [int(x) for x in rng.integers(1, 41, size=400)]
+    wl = synth.Workload("many-short", shape, nf, hush_frames=5, seed_index=11)
+    w, hush, mels = synth.materialize(wl)
+    ref, cu_ref = O.encode_batch(w, shape.n_heads, mels, hush)
+    for precision, tol in ((wf.WF_PRECISION_BF16, 2e-2), (wf.WF_PRECISION_F32, 1e-4)):
+        enc = wf.encoder_for_workload(wl, w, hush, precision)
+        flat, offs, n = wf.pack_mels(mels)
+        out, cu = enc.encode(torch.from_numpy(flat).cuda(), offs, n)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+        enc.close()
+        assert cu.tolist() == cu_ref.tolist()
+        assert H.rel_err(got, ref) <= tol
