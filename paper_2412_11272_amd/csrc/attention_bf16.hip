@@ -29,7 +29,8 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // K and V tiles are both kept row-major in LDS, [key][64 features] = 128-byte rows, 16-byte chunk c of
-// row r stored at chunk position c ^ ((r >> 1) & 7), and are filled straight from global memory by
+// row r stored at chunk position c ^ swizzle(r) (K: (r >> 1) & 7; V: v_swizzle(r), see there), and are
+// filled straight from global memory by
 // global_load_lds_dwordx4 (lane l of a wave lands at LDS base + 16 l, so a wave fills 8 rows per
 // instruction and applies the swizzle by choosing which chunk it fetches).
 //
@@ -43,6 +44,14 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // wholly in the future of a work item are never loaded, a wave skips the tiles that lie wholly in the
 // future of its 32 queries (tile starts and wave starts are multiples of 32, so every tile a wave does
 // process holds at least one visible key for each of its queries).
+// Chunk swizzle of a V row.  A transposing read touches 4 consecutive keys x 64 bytes (4 chunks), so rows r and
+// r + 2 -- same half of the 256-byte bank line -- must land in different groups of 4 chunks: the low bit of
+// (r >> 1) goes to bit 2 of the XOR mask.  (K rows keep (r >> 1) & 7, which suits 16-row b128 reads.)
+__device__ __forceinline__ int v_swizzle(int r) {
+  const int q = (r >> 1) & 7;
+  return ((q & 1) << 2) | (q >> 1);
+}
+
 template <bool CAUSAL>
 __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   __shared__ __attribute__((aligned(1024))) unsigned char sK[2][BKV * 128];
@@ -105,7 +114,7 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
       const int rt = (g & 7) * 8 + lrow;                // row inside the tile
       int key = kt * BKV + rt;
       key = key < L ? key : L - 1;                      // clamped rows are masked out of the softmax below
-      const int lch = (lane & 7) ^ ((rt >> 1) & 7);
+      const int lch = (lane & 7) ^ (g < 8 ? (rt >> 1) & 7 : v_swizzle(rt));
       const __bf16 *src = (g < 8 ? Kb : Vb) + (size_t)key * ld + lch * 8;
       unsigned char *dst = (g < 8 ? sK[buf] : sV[buf]) + (g & 7) * 1024;
       __builtin_amdgcn_global_load_lds((const glb_void *)src, (lds_void *)dst, 16, 0, 0);
@@ -209,9 +218,9 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
           const int k0 = kb2 * 32 + 16 * h + 4 * lg + tr_key;   // key row this lane addresses (first half)
           const int k1 = k0 + 8;
           const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4 *)(cV + k0 * 128 + ((fchunk ^ ((k0 >> 1) & 7)) << 4) + fin));
+              (lds_s16x4 *)(cV + k0 * 128 + ((fchunk ^ v_swizzle(k0)) << 4) + fin));
           const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4 *)(cV + k1 * 128 + ((fchunk ^ ((k1 >> 1) & 7)) << 4) + fin));
+              (lds_s16x4 *)(cV + k1 * 128 + ((fchunk ^ v_swizzle(k1)) << 4) + fin));
           const bf16x4 w0 = __builtin_bit_cast(bf16x4, v0), w1 = __builtin_bit_cast(bf16x4, v1);
           const bf16x8 vf = __builtin_shufflevector(w0, w1, 0, 1, 2, 3, 4, 5, 6, 7);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb2][h], o[t], 0, 0, 0);
