@@ -18,9 +18,11 @@ def _rel(got, ref):
     return float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
 
 
-# M spans: one partial small tile, several small tiles + ragged tail, and enough rows for the large tile
+# M spans: one partial small tile, several small tiles + ragged tail, enough rows for the large tile, and
+# (the last two) the row count of a 64-stream prompt prefill, where the small tile has to fill the chip
 @pytest.mark.parametrize("M,N,K", [(75, 384, 384), (300, 1152, 384), (1000, 128, 1536), (257, 256, 64),
-                                   (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280)])
+                                   (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280),
+                                   (6401, 1280, 1280), (6400, 1280, 5120)])
 @pytest.mark.parametrize("epi", [0, 1, 2])
 def test_linear_bf16(M, N, K, epi):
     import torch
