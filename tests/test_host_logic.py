@@ -89,6 +89,9 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert L.wf_encode_batch(None, None, 0, None, None, 1, None, 0, 0, None, None) == wf.WF_E_INVALID_ARG
     L.wf_encoder_destroy(None)                      # NULL-safe
     assert L.wf_kernel_class_count() >= 8
+    assert L.wf_encoder_set_lanes(None, 2) == wf.WF_E_INVALID_ARG
+    assert L.wf_encoder_get_lanes(None) == wf.WF_E_INVALID_ARG
+    assert "NULL" in wf.last_error()
 
 
 def test_workload_recipes():
