@@ -359,7 +359,11 @@ int wf_run_rounds(wf_rounds *r, wf_encoder *enc, const void *tracks_dev, int32_t
  * wf_beam_pruner_step receives the highest-probability token of one decoding step of the current round.
  *   - the beam size starts at 1;
  *   - a punctuation token (listed in punct_ids) or a timestamp / special token (id >= special_from) is
- *     skipped: beam and reference index stay as they are; such tokens are also left out of the reference;
+ *     skipped: beam and reference index stay as they are.  That is all the paper exempts (the current best
+ *     token).  With filter_reference != 0 such tokens are also left out of the reference list before any
+ *     matching, so that an ordinary token never meets a punctuation or timestamp token on the reference side
+ *     (an extension in the spirit of the rule's stated purpose); with filter_reference == 0 the reference is
+ *     matched exactly as handed over (the paper's literal rule);
  *   - the first ordinary token is searched in the reference; its first occurrence i aligns the session
  *     (the next ordinary token is compared with reference token i + 1), no occurrence falls back;
  *   - afterwards an ordinary token equal to the reference token at the index keeps the beam at 1 and
@@ -368,7 +372,8 @@ int wf_run_rounds(wf_rounds *r, wf_encoder *enc, const void *tracks_dev, int32_t
  * Events: 0 skipped, 1 aligned, 2 matched, 3 fallback (alignment failed), 4 fallback (mismatch),
  * 5 fallback (reference used up), 6 already at the original beam size.
  *
- * wf_beam_pruner_create   ref_tokens HOST [n_ref] (n_ref >= 0, copied), punct_ids HOST [n_punct] (copied).
+ * wf_beam_pruner_create   ref_tokens HOST [n_ref] (n_ref >= 0, copied), punct_ids HOST [n_punct] (copied);
+ *                         filter_reference: see above (it also applies to every later wf_beam_pruner_reset).
  * wf_beam_pruner_step     *event and *next_beam (either may be NULL): the event of this step and the beam
  *                         size the NEXT decoding step should run with.
  * wf_beam_pruner_reset    new decoding session against a new reference (same beam size and token classes).
@@ -377,7 +382,7 @@ int wf_run_rounds(wf_rounds *r, wf_encoder *enc, const void *tracks_dev, int32_t
  */
 typedef struct wf_beam_pruner wf_beam_pruner;
 int wf_beam_pruner_create(int32_t beam_size, const int32_t *ref_tokens, int32_t n_ref, int32_t special_from,
-                          const int32_t *punct_ids, int32_t n_punct, wf_beam_pruner **out);
+                          const int32_t *punct_ids, int32_t n_punct, int32_t filter_reference, wf_beam_pruner **out);
 int wf_beam_pruner_step(wf_beam_pruner *p, int32_t best_token, int32_t *event, int32_t *next_beam);
 int wf_beam_pruner_reset(wf_beam_pruner *p, const int32_t *ref_tokens, int32_t n_ref);
 int wf_beam_prune_session(wf_beam_pruner *p, const int32_t *best_tokens, int32_t n, int32_t *beam_for_step, int32_t *events);

@@ -12,10 +12,13 @@ step of the current round and receives that step's highest-probability token.
   3. Matching (later steps): the best token is compared with the reference token at the index.  Equal:
      beam stays 1, the index advances by one.  Different: fallback.
   4. Selectivity: if the best token is a punctuation, timestamp or any other special token, the step is
-     skipped: beam stays 1, the index does not move (this also holds before alignment).  The same kinds
-     of token are left out of the reference list: the paper's stated purpose of the rule is that
-     misplaced timestamps and punctuation must not disturb the matching, which they would if an ordinary
-     token could meet a punctuation token on the reference side.
+     skipped: beam stays 1, the index does not move (this also holds before alignment).  That is the
+     whole exemption the paper states: it concerns the CURRENT best token (filter_reference=False takes
+     it literally and matches against the reference exactly as the previous round left it).  With
+     filter_reference=True (the default) the same kinds of token are also left out of the reference list:
+     the paper's stated purpose of the rule is that misplaced timestamps and punctuation must not disturb
+     the matching, which they would if an ordinary token could meet a punctuation token on the reference
+     side.  This is an extension, not something the paper says.
   5. Fallback: the beam returns to the original size.
 
 Readings where the paper is silent: alignment waits for the first ordinary token (Whisper-style outputs
@@ -39,12 +42,13 @@ SKIPPED, ALIGNED, MATCHED, FB_ALIGN, FB_MISMATCH, FB_END, FULL = range(7)
 
 
 class BeamPruner:
-    def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Iterable[int] = ()):
+    def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Iterable[int] = (),
+                 filter_reference: bool = True):
         assert beam_size >= 1
         self.full = int(beam_size)
         self.special_from = int(special_from)
         self.punct = set(int(t) for t in punctuation)
-        self.ref = [int(t) for t in reference if not self.is_exempt(int(t))]
+        self.ref = [int(t) for t in reference if not (filter_reference and self.is_exempt(int(t)))]
         self.beam = 1
         self.idx = None            # reference index; None until aligned
         self.fallen = False
@@ -79,9 +83,9 @@ class BeamPruner:
 
 
 def run_session(beam_size: int, reference: Sequence[int], special_from: int, punctuation: Iterable[int],
-                best_tokens: Sequence[int]):
+                best_tokens: Sequence[int], filter_reference: bool = True):
     """Returns (beam_for_step, events): beam_for_step[t] = beam size step t ran with."""
-    p = BeamPruner(beam_size, reference, special_from, punctuation)
+    p = BeamPruner(beam_size, reference, special_from, punctuation, filter_reference)
     beams: List[int] = []
     events: List[int] = []
     for t in best_tokens:

@@ -152,7 +152,7 @@ def lib() -> C.CDLL:
     L.wf_rounds_end.argtypes = [C.c_void_p, C.c_int64, _lp]
     L.wf_rounds_get_stats.argtypes = [C.c_void_p, C.POINTER(WfRoundsStats)]
     L.wf_rounds_reset_stats.argtypes = [C.c_void_p]
-    L.wf_beam_pruner_create.argtypes = [C.c_int32, _ip, C.c_int32, C.c_int32, _ip, C.c_int32, C.POINTER(C.c_void_p)]
+    L.wf_beam_pruner_create.argtypes = [C.c_int32, _ip, C.c_int32, C.c_int32, _ip, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
     L.wf_beam_pruner_step.argtypes = [C.c_void_p, C.c_int32, _ip, _ip]
     L.wf_beam_pruner_reset.argtypes = [C.c_void_p, _ip, C.c_int32]
     L.wf_beam_prune_session.argtypes = [C.c_void_p, _ip, C.c_int32, _ip, _ip]
@@ -461,12 +461,14 @@ class Rounds:
 class BeamPruner:
     """Owns one wf_beam_pruner: the reference-based beam-size state machine (host only)."""
 
-    def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Sequence[int] = ()):
+    def __init__(self, beam_size: int, reference: Sequence[int], special_from: int, punctuation: Sequence[int] = (),
+                 filter_reference: bool = True):
         ref = np.ascontiguousarray(reference, dtype=np.int32)
         pun = np.ascontiguousarray(list(punctuation), dtype=np.int32)
         self._h = C.c_void_p(None)
         _check(lib().wf_beam_pruner_create(beam_size, ref.ctypes.data_as(_ip) if len(ref) else None, len(ref), special_from,
-                                           pun.ctypes.data_as(_ip) if len(pun) else None, len(pun), C.byref(self._h)))
+                                           pun.ctypes.data_as(_ip) if len(pun) else None, len(pun),
+                                           1 if filter_reference else 0, C.byref(self._h)))
 
     def step(self, best_token: int) -> Tuple[int, int]:
         ev, nb = C.c_int32(0), C.c_int32(0)

@@ -18,11 +18,12 @@ struct wf_beam_pruner {
   std::vector<int32_t> punct;                       // sorted
   int64_t idx = -1;                                 // reference index; -1 until aligned
   bool fallen = false;
+  bool filter_reference = true;                     // false: the reference list is matched as handed over
 
   void set_reference(const int32_t *t, int32_t n) {
     ref.clear();
     for (int32_t i = 0; i < n; ++i)
-      if (!exempt(t[i])) ref.push_back(t[i]);        // timestamps and punctuation take no part in the matching
+      if (!filter_reference || !exempt(t[i])) ref.push_back(t[i]);   // filtering: timestamps and punctuation take no part
     first_pos.clear();
     first_pos.reserve(ref.size() * 2 + 1);
     for (size_t i = 0; i < ref.size(); ++i) first_pos.emplace(ref[i], (int32_t)i);   // emplace keeps the first
@@ -57,7 +58,7 @@ struct wf_beam_pruner {
 extern "C" {
 
 int wf_beam_pruner_create(int32_t beam_size, const int32_t *ref_tokens, int32_t n_ref, int32_t special_from,
-                          const int32_t *punct_ids, int32_t n_punct, wf_beam_pruner **out) {
+                          const int32_t *punct_ids, int32_t n_punct, int32_t filter_reference, wf_beam_pruner **out) {
   if (!out) return fail(WF_E_INVALID_ARG, "out is NULL");
   *out = nullptr;
   if (beam_size < 1) return fail(WF_E_INVALID_ARG, "beam_size = %d, need >= 1", beam_size);
@@ -67,6 +68,7 @@ int wf_beam_pruner_create(int32_t beam_size, const int32_t *ref_tokens, int32_t 
   if (!p) return fail(WF_E_OOM, "host allocation failed");
   p->full = beam_size;
   p->special_from = special_from;
+  p->filter_reference = filter_reference != 0;
   p->punct.assign(punct_ids, punct_ids + n_punct);
   std::sort(p->punct.begin(), p->punct.end());
   p->set_reference(ref_tokens, n_ref);

@@ -5,12 +5,12 @@ import pytest
 
 from oracle import beam_prune_oracle as P
 from paper_2412_11272_amd import binding as wf
-from tests.test_beam_prune_pins import BEAM, PUNCT, SPECIAL_FROM, load_cases
+from tests.test_beam_prune_pins import BEAM, PUNCT, SPECIAL_FROM, filter_flag, load_cases
 
 
 def test_library_on_the_hand_worked_sessions():
     for c in load_cases():
-        bp = wf.BeamPruner(BEAM, c["ref"], SPECIAL_FROM, PUNCT)
+        bp = wf.BeamPruner(BEAM, c["ref"], SPECIAL_FROM, PUNCT, filter_reference=filter_flag(c))
         try:
             beams, events = bp.session(c["tok"])
             assert beams.tolist() == c["beam"], c["name"]
@@ -19,20 +19,21 @@ def test_library_on_the_hand_worked_sessions():
             bp.close()
 
 
+@pytest.mark.parametrize("filt", [True, False], ids=["filtered-reference", "literal-reference"])
 @pytest.mark.parametrize("seed", range(6))
-def test_library_matches_oracle_on_random_sessions(seed):
+def test_library_matches_oracle_on_random_sessions(seed, filt):
     rng = np.random.default_rng(500 + seed)
-    bp = wf.BeamPruner(BEAM, [], SPECIAL_FROM, PUNCT)
+    bp = wf.BeamPruner(BEAM, [], SPECIAL_FROM, PUNCT, filter_reference=filt)
     try:
         for _ in range(200):
-            ref = [int(t) for t in rng.integers(0, 95, size=int(rng.integers(0, 80)))]
+            ref = [int(t) for t in rng.integers(0, 110, size=int(rng.integers(0, 80)))]   # ordinary, punctuation and special ids
             n = int(rng.integers(0, 120))
             tok = [int(t) for t in rng.integers(0, 130, size=n)]
             if ref and rng.random() < 0.7:                        # overlap with the reference, lightly perturbed
                 a = int(rng.integers(0, len(ref)))
                 body = [t if rng.random() > 0.03 else int(rng.integers(0, 95)) for t in ref[a:]]
                 tok = ([100] if rng.random() < 0.5 else []) + body + tok[:10]
-            rb, re = P.run_session(BEAM, ref, SPECIAL_FROM, PUNCT, tok)
+            rb, re = P.run_session(BEAM, ref, SPECIAL_FROM, PUNCT, tok, filt)
             bp.reset(ref)
             beams, events = bp.session(tok)
             assert beams.tolist() == rb and events.tolist() == re

@@ -1,7 +1,11 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (bf16 path, bf16
-output, capacity sized for the workload).  The oracle encodes streams independently, so it is run on
-a sample of streams and compared with exactly those rows of the packed GPU output; size-independent
-properties are checked on every row."""
+output, capacity sized for the workload).  Every stream of the batch is encoded by the oracle and every
+row of the packed GPU output is compared with it: one global max|err| / max|ref| per configuration
+against the 2e-2 bar, and each stream's own ratio against twice that so that a bad short stream cannot
+hide behind a long one.  The oracle needs a few minutes for the large batch; progress lines are printed
+past pytest's capture."""
+import time
+
 import numpy as np
 import pytest
 
@@ -9,7 +13,7 @@ from oracle import encoder_oracle as O
 from paper_2412_11272_amd import binding as wf
 from tests import helpers as H
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
 
 def _run(name):
@@ -33,41 +37,46 @@ def _run(name):
         enc.close()
 
 
-def _properties(got, cu, lens):
-    assert np.all(np.isfinite(got))
+def _all_streams_parity(name, wl, w, hush, mels, got, cu, capsys):
+    """Oracle on every stream; returns (global ratio, worst per-stream ratio)."""
+    lens = [O.stem_length(len(m) + wl.hush_frames) for m in mels]
     assert cu.tolist() == np.concatenate([[0], np.cumsum(lens)]).tolist()
-    # final LayerNorm with unit gain: every row has mean 0 and variance var/(var+eps) just below 1 (bf16 output)
-    np.testing.assert_allclose(got.mean(axis=1), 0, atol=5e-3)
-    v = got.var(axis=1)
-    assert np.all(v > 0.97) and np.all(v < 1.01)
+    assert got.shape[0] == cu[-1] and np.all(np.isfinite(got))
+    w64 = O._cast(w, np.float64)
+    max_err = max_ref = 0.0
+    worst = (0.0, -1)
+    t0 = time.time()
+    for i, m in enumerate(mels):
+        ref = O.encode_stream(w64, wl.shape.n_heads, m, hush if wl.hush_frames > 0 else None, _cast_weights=False)
+        a = got[cu[i]:cu[i + 1]].astype(np.float64)
+        e, r = float(np.abs(a - ref).max()), float(np.abs(ref).max())
+        max_err, max_ref = max(max_err, e), max(max_ref, r)
+        if e / r > worst[0]:
+            worst = (e / r, i)
+        with capsys.disabled():
+            print(f"[{name}] stream {i + 1}/{len(mels)}: {lens[i]} tokens, rel err {e / r:.3e} ({time.time() - t0:.0f} s)", flush=True)
+    glob = max_err / max_ref
+    with capsys.disabled():
+        print(f"[{name}] all {len(mels)} streams, {cu[-1]} rows: global rel err {glob:.3e}, worst stream {worst[1]} "
+              f"({lens[worst[1]]} tokens) {worst[0]:.3e}", flush=True)
+    return glob, worst[0]
 
 
-def _sample_parity(name, picks, w, hush, mels, wl, got, cu):
-    worst = 0.0
-    for i in picks:
-        ref = O.encode_stream(w, wl.shape.n_heads, mels[i], hush if wl.hush_frames > 0 else None)
-        err = H.rel_err(got[cu[i]:cu[i + 1]], ref)
-        print(f"\n[{name}] stream {i}: {len(mels[i])} frames, {cu[i + 1] - cu[i]} tokens, rel err {err:.3e}", flush=True)
-        worst = max(worst, err)
-    assert worst <= H.BF16_TOL
-
-
-def test_cfg4_padded_window_vs_truncated():
+def test_cfg4_padded_window_vs_truncated(capsys):
     wl_a, w, hush_a, mels_a, got_a, cu_a = _run("cfg4a")
-    _properties(got_a, cu_a, [1500] * 8)                                  # 30 s windows -> 1500 tokens each
-    _sample_parity("cfg4a", [3], w, hush_a, mels_a, wl_a, got_a, cu_a)
+    assert np.diff(cu_a).tolist() == [1500] * 8                            # 30 s windows -> 1500 tokens each
+    glob, worst = _all_streams_parity("cfg4a", wl_a, w, hush_a, mels_a, got_a, cu_a, capsys)
+    assert glob <= H.BF16_TOL and worst <= 2 * H.BF16_TOL
     wl_b, w, hush_b, mels_b, got_b, cu_b = _run("cfg4b")
-    _properties(got_b, cu_b, [325] * 8)                                   # 6 s + hush -> 325 tokens each
-    _sample_parity("cfg4b", [0, 7], w, hush_b, mels_b, wl_b, got_b, cu_b)
+    assert np.diff(cu_b).tolist() == [325] * 8                             # 6 s + hush -> 325 tokens each
+    glob, worst = _all_streams_parity("cfg4b", wl_b, w, hush_b, mels_b, got_b, cu_b, capsys)
+    assert glob <= H.BF16_TOL and worst <= 2 * H.BF16_TOL
     assert np.array_equal(mels_a[0][:600], mels_b[0])                     # same payload, different tail
     # the padded window is attended to, so the two encodings legitimately differ
     assert np.abs(got_a[:300] - got_b[:300]).max() > 1e-2
 
 
-def test_cfg5_large_v3_ragged_batch():
+def test_cfg5_large_v3_ragged_batch(capsys):
     wl, w, hush, mels, got, cu = _run("cfg5")
-    lens = [(len(m) + wl.hush_frames + 1) // 2 for m in mels]
-    _properties(got, cu, lens)
-    order = np.argsort(lens)
-    picks = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]  # shortest, median, longest stream
-    _sample_parity("cfg5", picks, w, hush, mels, wl, got, cu)
+    glob, worst = _all_streams_parity("cfg5", wl, w, hush, mels, got, cu, capsys)
+    assert glob <= H.BF16_TOL and worst <= 2 * H.BF16_TOL
