@@ -5,6 +5,7 @@
 #include "host_runtime.h"
 
 #include <cmath>
+#include <mutex>
 #include <new>
 
 using namespace wf;
@@ -449,13 +450,39 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
   h_row0[0] = 0;
   for (int g = 0; g < n_lanes; ++g)
     h_row0[g + 1] = h_row0[g] + round_up(h_cu_seq[lane_b[g + 1]] - h_cu_seq[lane_b[g]], 256);
-  for (int g = n_lanes - 1; g >= 0; --g) {                 // the caller's own lane is enqueued last
+  // A failure part-way leaves kernels of the lanes already enqueued in flight on the encoder's own streams.  They
+  // are joined back into the caller's stream on every path, so that whatever the caller (or the next call on this
+  // encoder, which shares the workspace) enqueues on `s` afterwards is ordered after them.
+  int first_err = WF_OK;
+  char err_text[512] = "";
+  auto note = [&](int code) {
+    if (code != WF_OK && first_err == WF_OK) {
+      first_err = code;
+      snprintf(err_text, sizeof(err_text), "%s", g_err);
+    }
+  };
+  auto hip_note = [&](hipError_t err, const char *what) {
+    if (err != hipSuccess) note(fail(WF_E_HIP, "%s: %s", what, hipGetErrorString(err)));
+    return err == hipSuccess;
+  };
+  bool started[kMaxLanes] = {};
+  for (int g = n_lanes - 1; g >= 0 && first_err == WF_OK; --g) {   // the caller's own lane is enqueued last
     hipStream_t ls = g == 0 ? s : e->lane_stream[g];
-    if (g > 0) HIP_TRY(hipStreamWaitEvent(ls, e->fork_evt, 0));
-    if ((rc = run_lane(ls, lane_b[g], lane_b[g + 1], d_work + 2 * lane_w0[g], lane_w0[g + 1] - lane_w0[g], h_row0[g]))) return rc;
-    if (g > 0) HIP_TRY(hipEventRecord(e->lane_done[g], ls));
+    if (g > 0 && !hip_note(hipStreamWaitEvent(ls, e->fork_evt, 0), "lane fork")) break;
+    started[g] = g > 0;
+    note(run_lane(ls, lane_b[g], lane_b[g + 1], d_work + 2 * lane_w0[g], lane_w0[g + 1] - lane_w0[g], h_row0[g]));
   }
-  for (int g = 1; g < n_lanes; ++g) HIP_TRY(hipStreamWaitEvent(s, e->lane_done[g], 0));
+  for (int g = 1; g < n_lanes; ++g) {
+    if (!started[g]) continue;
+    if (hip_note(hipEventRecord(e->lane_done[g], e->lane_stream[g]), "lane join (record)"))
+      hip_note(hipStreamWaitEvent(s, e->lane_done[g], 0), "lane join (wait)");
+    else
+      (void)hipStreamSynchronize(e->lane_stream[g]);      // could not order it on the GPU: wait for it here
+  }
+  if (first_err != WF_OK) {
+    snprintf(g_err, sizeof(g_err), "%s", err_text);
+    return first_err;
+  }
   return WF_OK;
 }
 

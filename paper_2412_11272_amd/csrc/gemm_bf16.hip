@@ -27,6 +27,8 @@
 // weight panels and 8 activation panels instead of a whole row of weight panels, which cuts the L2 fill
 // traffic (the dominant off-chip energy of these kernels on a power-limited part) by more than half:
 // fc1 -7 %, QKV -2..-6 %.  Short rows (the 5 tile columns of the d x d and d x f projections) stay row-major.
+#include <mutex>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -212,23 +214,15 @@ template <int BM, int BN, int WM, int WN, int AMODE, int EPI>
 hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
   auto kern = gemm_bf16_kernel<BM, BN, WM, WN, AMODE, EPI>;
-  static bool attr_set = false;   // set once per process; device-wide limit, idempotent
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag once;          // raised LDS limit: set once per process, by whichever thread gets here first
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+  if (attr_err != hipSuccess) return attr_err;
+  // one workgroup per tile, rounded up to whole groups of 8 (XCD x takes tiles [x*per_xcd, (x+1)*per_xcd); the
+  // kernel drops the workgroups past the last tile)
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
-  GemmArgs b = a;
-  constexpr int kCUs = 256;
-  const int rest = tiles % kCUs;
-  const bool split = rest > 0 && 2 * rest <= kCUs;
-  b.n_full = split ? tiles - rest : tiles;
-  b.n_half = split ? 2 * rest : 0;
-  b.full_per_xcd = (b.n_full + 7) / 8;
-  b.half_per_xcd = (b.n_half + 7) / 8;
-  const int grid = 8 * (b.full_per_xcd + b.half_per_xcd);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
+  const int grid = 8 * ((tiles + 7) / 8);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
   return hipGetLastError();
 }
 
@@ -609,12 +603,10 @@ template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = 
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
   auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT, AMODE, DEEP>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+  if (attr_err != hipSuccess) return attr_err;
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   GemmArgs b = a;
   constexpr int kCUs = 256;
