@@ -191,6 +191,21 @@ int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, 
                     int32_t M, int32_t d, float eps, void *hip_stream);
 int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
                     int32_t n_heads, void *hip_stream);
+/*
+ * wf_op_attention for callers that cannot allocate device memory (code that a HIP graph capture may enclose,
+ * tight serving loops, harnesses that forbid hipMalloc).  Same arguments, same kernels and bit-identical
+ * results, but: it calls no hipMalloc / hipFree / hipMemcpy / hipMemset and no allocating routine of any
+ * library; the prefix sums and the work list go into a 64 KiB device array that is part of the library image
+ * (one copy per GPU, held until the process ends) and reach it as kernel arguments of a small fill kernel; and it
+ * is asynchronous on hip_stream (no wait before returning).
+ * Limit: B + 1 + 2 * sum_i ceil(L_i / 128) <= 16384 ints (L_i = tokens of stream i), i.e. about 1 M tokens in
+ * long streams or 5461 one-block streams; beyond it the call returns WF_E_CAPACITY with the sizes in
+ * wf_last_error() and launches nothing.
+ * All calls on one GPU share that array: calls ordered on one stream are safe back to back (each rewrites every
+ * entry it reads; nothing has to start at zero), calls that overlap on different streams of one GPU race.
+ */
+int wf_op_attention_noalloc(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
+                            int32_t n_heads, void *hip_stream);
 
 /*
  * Log-mel front end with the hush word appended at the raw-audio level (the step right before the

@@ -100,7 +100,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_encoder_get_config", "wf_encoder_set_lanes", "wf_encoder_get_lanes", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
-           "wf_beam_pruner_destroy"]
+           "wf_beam_pruner_destroy", "wf_op_attention_noalloc"]
 
 
 def lib() -> C.CDLL:
@@ -129,6 +129,7 @@ def lib() -> C.CDLL:
     L.wf_op_layernorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_float, C.c_void_p]
     L.wf_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, _ip, C.c_int32, C.c_int32, C.c_void_p]
+    L.wf_op_attention_noalloc.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, _ip, C.c_int32, C.c_int32, C.c_void_p]
     L.wf_frontend_create.argtypes = [C.POINTER(WfFrontendConfig), C.c_void_p, C.POINTER(C.c_void_p)]
     L.wf_logmel_batch.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), _ip, C.c_int32, C.c_void_p, C.c_int32,
                                   C.c_int64, _ip, C.c_void_p]
@@ -548,4 +549,14 @@ def op_attention(precision: int, qkv, out, cu_seqlens: Sequence[int], n_heads: i
     s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
     _check(lib().wf_op_attention(precision, C.c_void_p(qkv.data_ptr()), C.c_void_p(out.data_ptr()), cu.ctypes.data_as(_ip),
                                  len(cu) - 1, n_heads, C.c_void_p(s)))
+    return out
+
+
+def op_attention_noalloc(precision: int, qkv, out, cu_seqlens: Sequence[int], n_heads: int, stream=None):
+    """wf_op_attention_noalloc: same result as op_attention, no device allocation, asynchronous on the stream."""
+    import torch
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().wf_op_attention_noalloc(precision, C.c_void_p(qkv.data_ptr()), C.c_void_p(out.data_ptr()), cu.ctypes.data_as(_ip),
+                                         len(cu) - 1, n_heads, C.c_void_p(s)))
     return out

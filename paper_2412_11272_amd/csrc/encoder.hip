@@ -572,6 +572,91 @@ int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const
 
 }  // extern "C"
 
+// ------------------------------------------------------------------------------------------------
+// wf_op_attention for callers that cannot allocate: the index memory (prefix sums + work list) that
+// wf_op_attention gets from hipMalloc lives in a file-scope device array instead.
+namespace {
+
+constexpr int kScratchInts = 16384;                       // 64 KiB per GPU, held until the process ends
+static __device__ __align__(256) int32_t scratch[kScratchInts];
+
+constexpr int kMaxDevices = 16;
+int32_t *g_scratch_ptr[kMaxDevices] = {};                 // device address of `scratch` on each GPU (the array's
+std::mutex g_scratch_mu;                                  // name is only a host-side stand-in for the symbol)
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+int scratch_address(int32_t **out) {
+  int dev = 0;
+  WF_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(WF_E_INVALID_ARG, "device %d: only devices 0 .. %d are supported", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    WF_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(WF_E_HIP, "hipGetSymbolAddress returned a NULL address");
+    g_scratch_ptr[dev] = (int32_t *)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return WF_OK;
+}
+
+// Host -> device transport of a few hundred ints without a copy engine, a staging buffer or a memset: the
+// values ride in the kernel arguments.
+constexpr int kFillChunk = 960;                           // ints per launch (kernel arguments are limited to 4 KiB)
+struct FillArgs {
+  int32_t n;
+  int32_t v[kFillChunk];
+};
+__global__ void __launch_bounds__(256) fill_ints_kernel(int32_t *dst, FillArgs a) {
+  for (int i = threadIdx.x; i < a.n; i += blockDim.x) dst[i] = a.v[i];
+}
+
+}  // namespace
+
+extern "C" int wf_op_attention_noalloc(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
+                                       int32_t n_heads, void *hip_stream) {
+  if (!qkv_dev || !out_dev || !cu_seqlens_host) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (precision != WF_PRECISION_BF16 && precision != WF_PRECISION_F32) return fail(WF_E_INVALID_ARG, "precision = %d", precision);
+  if (B < 1 || n_heads < 1 || cu_seqlens_host[0] != 0) return fail(WF_E_INVALID_ARG, "need B >= 1, n_heads >= 1, cu_seqlens[0] == 0");
+  constexpr int kMaxB = (kScratchInts - 1) / 3;          // every stream needs its prefix sum and at least one work item
+  if (B > kMaxB) return fail(WF_E_CAPACITY, "B = %d exceeds the %d streams the %d-int index scratch can hold", B, kMaxB, kScratchInts);
+  for (int i = 0; i < B; ++i)
+    if (cu_seqlens_host[i + 1] <= cu_seqlens_host[i] || cu_seqlens_host[i + 1] - cu_seqlens_host[i] > (1 << 20))
+      return fail(WF_E_INVALID_ARG, "stream %d: need 1 .. %d tokens", i, 1 << 20);
+  const int M = cu_seqlens_host[B];
+  const int qt = attention_q_tile();
+  int64_t n_work = 0;
+  for (int i = 0; i < B; ++i) n_work += (cu_seqlens_host[i + 1] - cu_seqlens_host[i] + qt - 1) / qt;
+  const int64_t need = (int64_t)(B + 1) + 2 * n_work;
+  if (need > kScratchInts)
+    return fail(WF_E_CAPACITY, "B = %d streams with %lld query blocks need %lld ints of index scratch, the limit is %d "
+                "(B + 1 + 2 * sum ceil(L_i / %d) <= %d); use wf_op_attention", B, (long long)n_work, (long long)need, kScratchInts, qt, kScratchInts);
+  int32_t *d_idx = nullptr;
+  int rc = scratch_address(&d_idx);
+  if (rc) return rc;
+  int32_t idx[kScratchInts];                              // host copy of the indices, on the stack: no heap use either
+  int64_t keys[kMaxB];
+  memcpy(idx, cu_seqlens_host, (size_t)(B + 1) * 4);
+  const int nw = build_work_noalloc(cu_seqlens_host, B, qt, idx + B + 1, keys);
+  hipStream_t s = (hipStream_t)hip_stream;
+  for (int64_t off = 0; off < need; off += kFillChunk) {  // every entry this call reads is rewritten; nothing needs clearing
+    FillArgs fa;
+    fa.n = (int32_t)std::min<int64_t>(kFillChunk, need - off);
+    memcpy(fa.v, idx + off, (size_t)fa.n * 4);
+    hipLaunchKernelGGL(fill_ints_kernel, dim3(1), dim3(256), 0, s, d_idx + off, fa);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return fail(WF_E_HIP, "index fill launch: %s", hipGetErrorString(err));
+  }
+  AttnArgs a{};
+  const size_t es = precision == WF_PRECISION_BF16 ? 2 : 4;
+  a.q = qkv_dev; a.k = (const char *)qkv_dev + (size_t)n_heads * 64 * es; a.v = (const char *)qkv_dev + (size_t)2 * n_heads * 64 * es;
+  a.ldq = a.ldkv = 3 * n_heads * 64; a.out = out_dev; a.cu_q = a.cu_kv = d_idx; a.work = d_idx + B + 1;
+  a.n_work = nw; a.n_heads = n_heads; a.d_model = n_heads * 64; a.B = B; a.M = M; a.scale = 0.125f;
+  hipError_t err = precision == WF_PRECISION_BF16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s);
+  if (err != hipSuccess) return fail(WF_E_HIP, "attention launch: %s", hipGetErrorString(err));
+  return WF_OK;
+}
+
 namespace wf {
 hipError_t init_kernels() { return hipSuccess; }
 }  // namespace wf

@@ -257,5 +257,24 @@ inline int build_work(const int32_t *cu_q, int B, int q_tile, int32_t *work, con
   return n;
 }
 
+// Same work list as build_work (streams by descending query count, ties in input order) without touching the
+// heap: `keys` is caller-provided room for B entries.  Each key packs (count, B - 1 - index), so sorting the keys
+// in descending order is the stable descending sort by count.
+inline int build_work_noalloc(const int32_t *cu_q, int B, int q_tile, int32_t *work, int64_t *keys) {
+  for (int i = 0; i < B; ++i) keys[i] = ((int64_t)(cu_q[i + 1] - cu_q[i]) << 32) | (uint32_t)(B - 1 - i);
+  std::sort(keys, keys + B, [](int64_t a, int64_t b) { return a > b; });   // introsort: in place
+  int n = 0;
+  for (int rank = 0; rank < B; ++rank) {
+    const int i = B - 1 - (int)(keys[rank] & 0xffffffff);
+    const int Lq = cu_q[i + 1] - cu_q[i];
+    for (int q0 = 0; q0 < Lq; q0 += q_tile) {
+      work[2 * n] = i;
+      work[2 * n + 1] = q0 | ((rank & 7) << 20);
+      ++n;
+    }
+  }
+  return n;
+}
+
 }  // namespace host
 }  // namespace wf
