@@ -63,6 +63,67 @@ def cpu_baseline(wl, weights, hush, mels, budget_flops=6e12):
                       f"NumPy fp64 oracle, {dt:.1f} s wall, {fl / dt / 1e9:.1f} GFLOP/s"}
 
 
+def bench_small_config(name, steps, warmup):
+    """One of the other benchmark configurations through the same entry point: median of per-call HIP-event times
+    (these calls are short, so the wall clock over a loop would mostly measure the host)."""
+    import torch
+    from paper_2412_11272_amd import binding as wf
+    from paper_2412_11272_amd import synth
+    wl = synth.workload(name)
+    weights, hush, mels = synth.materialize(wl)
+    enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)
+    flat, offs, nf = wf.pack_mels(mels)
+    mel = torch.from_numpy(flat).cuda()
+    cu, total_frames, M = wf.plan_batch(enc.cfg, nf)
+    out = torch.empty((M, wl.shape.d_model), device="cuda", dtype=torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed():
+        for _ in range(warmup):
+            enc.encode(mel, offs, nf, out=out, stream=stream)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record()
+            enc.encode(mel, offs, nf, out=out, stream=stream)
+            e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps * 1e3
+        per_call = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return per_call[len(per_call) // 2], wall
+
+    ms, wall = timed()
+    ms_graph = None
+    if enc.get_lanes() >= 1 and M < 8192:          # one-lane batches can be replayed from a captured graph (opt-in)
+        enc.set_graphs(True)
+        ms_graph, _ = timed()
+        if enc.graph_stats()["replays"] == 0:
+            ms_graph = None
+        enc.set_graphs(False)
+    enc.close()
+    flops = algorithmic_flops(wl.shape, wl.hush_frames, nf)
+    payload = float(sum(wl.n_frames)) / synth.FRAMES_PER_SECOND          # seeded audio only: the padding of cfg4a is not payload
+    return {"streams": len(nf), "tokens": int(M), "ms": round(ms, 4), "ms_wall_mean": round(wall, 4),
+            "ms_graph_replay": None if ms_graph is None else round(ms_graph, 4),
+            "tokens_per_s": round(M / ms * 1e3, 1), "audio_s_per_s": round(payload / ms * 1e3, 1),
+            "algorithmic_gflop": round(flops / 1e9, 2),
+            "pct_bf16_mfma_peak": round(100.0 * flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)}
+
+
+def bench_configs(steps, warmup):
+    """Every benchmark configuration besides the headline one, plus the tokens-saved speed-up of the truncated
+    buffer over the padded 30 s window (same 8 streams, same payload)."""
+    res = {}
+    for name in ("cfg1", "cfg2-2s", "cfg2-4s", "cfg2-8s", "cfg3", "cfg4a", "cfg4b"):
+        res[name] = bench_small_config(name, max(steps, 30) if name < "cfg4" else steps, warmup)
+    a, b = res["cfg4a"], res["cfg4b"]
+    res["cfg4_padded_over_truncated"] = {"time_ratio_t4a_over_t4b": round(a["ms"] / b["ms"], 2),
+                                         "flop_ratio": round(a["algorithmic_gflop"] / b["algorithmic_gflop"], 2),
+                                         "token_ratio": round(a["tokens"] / b["tokens"], 2)}
+    return res
+
+
 def bench_frontend(wl, n_frames, steps, warmup):
     """Raw 16 kHz audio of the workload's lengths + the 8000-sample hush word -> packed log-mel (not part of `value`)."""
     import numpy as np
@@ -238,11 +299,14 @@ def main():
                     help="processing rounds per step length through the round driver (default 8; 0 with --encoder-only)")
     ap.add_argument("--beam-sessions", type=int, default=-1,
                     help="synthetic decoding sessions for the beam-pruning state machine, host only (default 2000; 0 with --encoder-only)")
+    ap.add_argument("--configs", action="store_true",
+                    help="with --encoder-only: also time the other benchmark configurations (cfg1 .. cfg4b); on by default otherwise")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     legs = not args.encoder_only and args.workload == "cfg5"
     args.frontend = args.frontend or legs
+    args.configs = args.configs or legs
     args.prefill = args.prefill or legs
     if args.rounds < 0:
         args.rounds = 8 if legs else 0
@@ -259,6 +323,12 @@ def main():
     from paper_2412_11272_amd import synth
 
     torch.cuda.set_device(0)
+    prop = torch.cuda.get_device_properties(0)
+    # dense bf16 MFMA peak = CUs x 4096 flop per clock x clock; the published 2.5 PFLOP/s is 256 CUs at 2.4 GHz and is
+    # what every fraction here is quoted against, whatever the device reports
+    peak_note = {"used_tflops": PEAK_BF16_TFLOPS, "device": prop.name, "compute_units": int(prop.multi_processor_count),
+                 "max_clock_ghz": round(getattr(prop, "clock_rate", 0) / 1e6, 3),
+                 "from_device_tflops": round(prop.multi_processor_count * 4096 * getattr(prop, "clock_rate", 0) * 1e3 / 1e12, 1)}
     wl = synth.workload(args.workload)
     weights, hush, mels = synth.materialize(wl)
     enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)
@@ -291,6 +361,16 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
 
+    # the same call timed one by one with an event pair each (median: robust against a host hiccup in the loop)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_call = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    ms_median = per_call[len(per_call) // 2]
+
     # same steps again with every launch bracketed by HIP events on the launch stream, on ONE lane so that a
     # kernel's duration is its own: with more lanes kernels of different groups overlap
     enc.set_lanes(1)
@@ -318,15 +398,20 @@ def main():
     mfma = [s for s in stats if s["flops"] > 0 and s["launches"] > 0]
     dom = max(mfma, key=lambda s: s["total_ms"])
     achieved = dom["flops"] / dom["total_ms"] / 1e9          # TFLOP/s
-    traffic = None
+    # HBM-side bytes cannot be counted from inside this process: the figure is the one recorded by the rocprofv3 --pmc
+    # runs of this same command (profiles/traffic.json, with the commit it was taken at), not a measurement of this run
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom["name"], {}).get("total_bytes")
+            tj = json.load(open(tpath))
+            traffic = tj.get(args.workload, {}).get(dom["name"], {}).get("total_bytes")
+            traffic_src = f"profiles/traffic.json ({tj.get('_recorded_at', 'commit not recorded')})"
         except Exception:
             traffic = None
     roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_unit": "bytes per launch (L2 fill + write-back, rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, calibrated)",
+                "traffic_source": traffic_src,
                 "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
                 "avg_launch_ms": round(dom["total_ms"] / dom["launches"], 4),
                 "flops_per_launch": dom["flops"] / dom["launches"],
@@ -337,6 +422,7 @@ def main():
         "metric": "encoded audio-sec/sec & tokens/sec per GPU; % of bf16 MFMA peak",
         "value": round(payload_audio_s / dt, 1), "unit": "audio-s/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 3),
+        "ms_per_step_median_of_event_timed_calls": round(ms_median, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: large-v3-shaped encoder, 64 ragged streams" if wl.name == "cfg5" else wl.name,
                    "streams": len(nf), "tokens": int(M), "frames_incl_hush": int(total_frames),
@@ -346,12 +432,18 @@ def main():
         "audio_s_per_s_incl_hush": round(total_frames / synth.FRAMES_PER_SECOND / dt, 1),
         "algorithmic_tflops": round(flops / dt / 1e12, 1),
         "pct_bf16_mfma_peak": round(100.0 * flops / dt / 1e12 / PEAK_BF16_TFLOPS, 2),
+        "peak": peak_note,
         "roofline": roofline,
         "kernels": kernels,
     }
     if args.frontend:
         result["frontend"] = bench_frontend(wl, nf, args.steps, args.warmup)
     enc.close()
+    if args.configs:
+        del mel
+        mel = None
+        torch.cuda.empty_cache()
+        result["configs"] = bench_configs(args.steps, args.warmup)
     if args.prefill:
         result["prefill"] = bench_prefill(wl, out, cu, args.steps, args.warmup)
     del mel, out

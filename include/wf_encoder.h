@@ -166,6 +166,21 @@ int wf_encoder_kernel_stats(wf_encoder *enc, wf_kernel_stat *stats, int32_t n_st
  * call's work counts as done.  wf_encoder_get_lanes returns the current setting (negative WF_E_* on error). */
 int wf_encoder_set_lanes(wf_encoder *enc, int32_t n_lanes);
 int wf_encoder_get_lanes(const wf_encoder *enc);
+/* Replay of small batches (opt-in, default off).  A batch that runs on one lane (fewer than 8192 tokens) consists
+ * of 4 + 7 n_layers short dependent kernels (paper, Section "Operations": one stream's buffer per round is the
+ * method's own case, 75 .. 750 tokens).  With wf_encoder_set_graphs(enc, 1), wf_encode_batch keeps up to 64 captured
+ * HIP graphs of that launch sequence, keyed on everything that shapes the launches or is baked into their arguments: B, every
+ * n_frames[i] and frame_offset[i], mel_dev, out_dev and the two dtypes.  A key seen for the second time is captured
+ * (on a stream of the encoder, never the caller's; no memset or memcpy node: each entry owns a device copy of its
+ * index arrays) and replayed from then on with one hipGraphLaunch on hip_stream; other calls, all batches with
+ * more lanes, the fp32 path and calls under wf_encoder_set_profiling launch kernel by kernel.  Results are
+ * bit-identical either way.  It takes the per-launch work off the host thread (one call instead of dozens); the time
+ * on the GPU is the same, because a kernel of a dependent chain starts 5 - 7 us after its predecessor however it was
+ * submitted.  The caller's buffers are part of the key, so a replay reads and writes the same
+ * addresses the capture saw: keep mel_dev / out_dev allocated while replay is on.  wf_encoder_graph_stats: calls replayed, graphs captured, calls launched
+ * directly (any pointer may be NULL). */
+int wf_encoder_set_graphs(wf_encoder *enc, int32_t enabled);
+int wf_encoder_graph_stats(const wf_encoder *enc, int64_t *replays, int64_t *captures, int64_t *direct_calls);
 /* The configuration the encoder was created with (ln_eps as resolved). */
 int wf_encoder_get_config(const wf_encoder *enc, wf_config *cfg);
 

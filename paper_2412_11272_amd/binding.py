@@ -100,7 +100,8 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_encoder_get_config", "wf_encoder_set_lanes", "wf_encoder_get_lanes", "wf_rounds_create", "wf_rounds_begin", "wf_rounds_end", "wf_rounds_get_stats", "wf_rounds_reset_stats",
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
-           "wf_beam_pruner_destroy", "wf_op_attention_noalloc"]
+           "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats"]
 
 
 def lib() -> C.CDLL:
@@ -147,7 +148,9 @@ def lib() -> C.CDLL:
     L.wf_encoder_get_config.argtypes = [C.c_void_p, C.POINTER(WfConfig)]
     L.wf_encoder_set_lanes.argtypes = [C.c_void_p, C.c_int32]
     L.wf_encoder_get_lanes.argtypes = [C.c_void_p]
+    L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
+    L.wf_encoder_graph_stats.argtypes = [C.c_void_p, _lp, _lp, _lp]
     L.wf_rounds_create.argtypes = [C.POINTER(WfRoundsConfig), _lp, C.POINTER(C.c_void_p)]
     L.wf_rounds_begin.argtypes = [C.c_void_p, _lp, _ip, _ip]
     L.wf_rounds_end.argtypes = [C.c_void_p, C.c_int64, _lp]
@@ -248,6 +251,14 @@ class Encoder:
 
     def set_lanes(self, n: int):
         _check(lib().wf_encoder_set_lanes(self._h, int(n)))
+
+    def set_graphs(self, enabled: bool):
+        _check(lib().wf_encoder_set_graphs(self._h, 1 if enabled else 0))
+
+    def graph_stats(self) -> dict:
+        r, c, d = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+        _check(lib().wf_encoder_graph_stats(self._h, C.byref(r), C.byref(c), C.byref(d)))
+        return {"replays": r.value, "captures": c.value, "direct_calls": d.value}
 
     def get_lanes(self) -> int:
         n = lib().wf_encoder_get_lanes(self._h)

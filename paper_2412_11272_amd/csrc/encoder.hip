@@ -68,7 +68,22 @@ struct wf_encoder : DevCtx {
   int32_t *frame_src = nullptr, *frame_flags = nullptr, *tok_src = nullptr, *tok_flags = nullptr, *tok_pos = nullptr;
   int32_t *idx_dev = nullptr;
   int64_t idx_ints = 0;
+  // Replay cache for small batches (see wf_encoder_set_graphs): launch sequences captured as HIP graphs, keyed on
+  // everything that shapes the launches or is baked into their arguments.
+  struct GraphEntry {
+    std::vector<int64_t> key;
+    int32_t *idx = nullptr;              // this entry's own copy of the index arrays (device)
+    hipGraphExec_t exec = nullptr;       // NULL: key seen once, nothing captured yet
+    uint64_t last_use = 0;
+  };
+  std::vector<GraphEntry> graphs;
+  bool graphs_enabled = false;
+  hipStream_t cap_stream = nullptr;      // capture happens here, never on the caller's stream
+  uint64_t graph_clock = 0;
+  int64_t graph_replays = 0, graph_captures = 0, direct_calls = 0;
 };
+
+constexpr int kGraphCacheEntries = 64;
 
 namespace {
 
@@ -161,6 +176,13 @@ int wf_kernel_class_count(void) { return KC_COUNT; }
 
 void wf_encoder_destroy(wf_encoder *e) {
   if (!e) return;
+  (void)hipSetDevice(e->device);
+  (void)hipDeviceSynchronize();
+  for (auto &g : e->graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.idx) (void)hipFree(g.idx);
+  }
+  if (e->cap_stream) (void)hipStreamDestroy(e->cap_stream);
   release(e);
   for (int g = 1; g < kMaxLanes; ++g) {
     if (e->lane_stream[g]) (void)hipStreamDestroy(e->lane_stream[g]);
@@ -268,6 +290,7 @@ static int create_impl(wf_encoder *e, const wf_config *cfg, const wf_weights *w)
     HIP_TRY(hipEventCreateWithFlags(&e->lane_done[g], hipEventDisableTiming));
   }
   HIP_TRY(hipEventCreateWithFlags(&e->fork_evt, hipEventDisableTiming));
+  HIP_TRY(hipStreamCreateWithFlags(&e->cap_stream, hipStreamNonBlocking));
   HIP_TRY(hipDeviceSynchronize());
   return WF_OK;
 }
@@ -344,11 +367,12 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
   const int n_work = lane_w0[n_lanes];
   if (cu_seqlens_host) memcpy(cu_seqlens_host, h_cu_seq, (size_t)(B + 1) * 4);
 
-  hipStream_t s = (hipStream_t)hip_stream;
   const size_t idx_bytes = (size_t)(4 * S1 + 2 * n_work) * 4;
-  if ((rc = staging_submit(e, slot, e->idx_dev, idx_bytes, s))) return rc;
-  const int32_t *d_cu_frames = e->idx_dev, *d_cu_seq = e->idx_dev + S1, *d_off = e->idx_dev + 2 * S1, *d_nf = e->idx_dev + 3 * S1,
-                *d_work = e->idx_dev + 4 * S1;
+
+  // The launch sequence on stream s, reading the index arrays at idx_base (device).
+  auto enqueue = [&](hipStream_t s, const int32_t *idx_base) -> int {
+  const int32_t *d_cu_frames = idx_base, *d_cu_seq = idx_base + S1, *d_off = idx_base + 2 * S1, *d_nf = idx_base + 3 * S1,
+                *d_work = idx_base + 4 * S1;
 
   const int d = c.d_model, f = c.d_mlp, C = c.n_mels;
   const int act_bf16 = e->bf16 ? 1 : 0;
@@ -483,6 +507,98 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     snprintf(g_err, sizeof(g_err), "%s", err_text);
     return first_err;
   }
+  return WF_OK;
+  };   // enqueue
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  // ---- small batches: replay a captured graph of the same launch sequence.  A batch of a few thousand tokens is
+  // bound by the cost of issuing its 4 + 7 n_layers launches one by one; everything that shapes those launches or is
+  // baked into their arguments (stream lengths and offsets, the two caller buffers, the dtypes) is the cache key, so
+  // a replay needs no upload at all: each entry keeps its own device copy of the index arrays.  A key is captured
+  // the second time it is seen; other batches take the direct path below.
+  const bool graph_ok = e->graphs_enabled && e->bf16 && !e->profiling && n_lanes == 1;
+  if (graph_ok) {
+    std::vector<int64_t> key;
+    key.reserve(2 * (size_t)B + 5);
+    key.push_back(B);
+    key.push_back((int64_t)(uintptr_t)mel_dev);
+    key.push_back((int64_t)(uintptr_t)out_dev);
+    key.push_back(mel_dtype);
+    key.push_back(out_dtype);
+    for (int i = 0; i < B; ++i) key.push_back(((int64_t)frame_offset[i] << 32) | (uint32_t)n_frames[i]);
+    wf_encoder::GraphEntry *hit = nullptr;
+    for (auto &g : e->graphs)
+      if (g.key == key) { hit = &g; break; }
+    if (hit && hit->exec) {
+      hit->last_use = ++e->graph_clock;
+      HIP_TRY(hipGraphLaunch(hit->exec, s));
+      ++e->graph_replays;
+      return WF_OK;
+    }
+    if (!hit) {                                   // first sighting: remember the key, run directly
+      if ((int)e->graphs.size() >= kGraphCacheEntries) {
+        size_t victim = 0;
+        for (size_t i = 1; i < e->graphs.size(); ++i)
+          if (e->graphs[i].last_use < e->graphs[victim].last_use) victim = i;
+        wf_encoder::GraphEntry &v = e->graphs[victim];
+        if (v.exec) {                             // may still be in flight: wait before tearing it down
+          HIP_TRY(hipDeviceSynchronize());
+          (void)hipGraphExecDestroy(v.exec);
+          (void)hipFree(v.idx);
+        }
+        e->graphs.erase(e->graphs.begin() + (long)victim);
+      }
+      wf_encoder::GraphEntry g;
+      g.key = std::move(key);
+      g.last_use = ++e->graph_clock;
+      e->graphs.push_back(std::move(g));
+    } else {                                      // second sighting: capture, instantiate, replay
+      hit->last_use = ++e->graph_clock;
+      int32_t *idx = nullptr;
+      HIP_TRY(hipMalloc((void **)&idx, idx_bytes));
+      hipError_t err = hipMemcpy(idx, hs, idx_bytes, hipMemcpyHostToDevice);
+      hipGraph_t graph = nullptr;
+      hipGraphExec_t exec = nullptr;
+      int erc = WF_OK;
+      if (err == hipSuccess) err = hipStreamBeginCapture(e->cap_stream, hipStreamCaptureModeThreadLocal);
+      if (err == hipSuccess) {
+        erc = enqueue(e->cap_stream, idx);
+        err = hipStreamEndCapture(e->cap_stream, &graph);          // always ends the capture, also after a failed launch
+        if (err == hipSuccess && erc == WF_OK) err = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        if (graph) (void)hipGraphDestroy(graph);
+      }
+      if (err != hipSuccess || erc != WF_OK || !exec) {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        (void)hipFree(idx);
+        (void)hipGetLastError();
+        if (erc != WF_OK) return erc;
+        if (err != hipSuccess) return fail(WF_E_HIP, "graph capture: %s", hipGetErrorString(err));
+        return fail(WF_E_HIP, "graph capture produced no executable graph");
+      }
+      hit->idx = idx;
+      hit->exec = exec;
+      ++e->graph_captures;
+      HIP_TRY(hipGraphLaunch(exec, s));
+      ++e->graph_replays;
+      return WF_OK;
+    }
+  }
+  ++e->direct_calls;
+  if ((rc = staging_submit(e, slot, e->idx_dev, idx_bytes, s))) return rc;
+  return enqueue(s, e->idx_dev);
+}
+
+int wf_encoder_set_graphs(wf_encoder *e, int32_t enabled) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  e->graphs_enabled = enabled != 0;
+  return WF_OK;
+}
+
+int wf_encoder_graph_stats(const wf_encoder *e, int64_t *replays, int64_t *captures, int64_t *direct_calls) {
+  if (!e) return fail(WF_E_INVALID_ARG, "encoder is NULL");
+  if (replays) *replays = e->graph_replays;
+  if (captures) *captures = e->graph_captures;
+  if (direct_calls) *direct_calls = e->direct_calls;
   return WF_OK;
 }
 
