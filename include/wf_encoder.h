@@ -185,6 +185,16 @@ int wf_encoder_graph_stats(const wf_encoder *enc, int64_t *replays, int64_t *cap
 int wf_encoder_get_config(const wf_encoder *enc, wf_config *cfg);
 
 /*
+ * Diagnostic, host only (no GPU call): the work units the MFMA GEMM launches for an M x N result with tile_m x tile_n
+ * tiles, in workgroup order, as (first row, first column, width in columns) triples in units[3 * i .. 3 * i + 2]
+ * (HOST, room for `capacity` triples).  Whole tiles first; the tiles left over after the last full round of the
+ * chip are cut into two half-width units when that shortens the last round.  It runs the very code the kernel
+ * uses to decode its workgroup id, so a test can check that every element of the result is covered exactly once.
+ * Returns the number of units (>= 0) or a negative WF_E_* code.
+ */
+int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32_t *units, int32_t capacity);
+
+/*
  * Operator-level entry points: single steps of the encoder on caller-provided DEVICE buffers, for
  * per-operator checks and micro-benchmarks.  precision selects the kernel family and the element
  * type of activations and weights (WF_PRECISION_BF16: bf16, WF_PRECISION_F32: fp32).

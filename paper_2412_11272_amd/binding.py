@@ -101,7 +101,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
-           "wf_encoder_set_graphs", "wf_encoder_graph_stats"]
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map"]
 
 
 def lib() -> C.CDLL:
@@ -148,6 +148,7 @@ def lib() -> C.CDLL:
     L.wf_encoder_get_config.argtypes = [C.c_void_p, C.POINTER(WfConfig)]
     L.wf_encoder_set_lanes.argtypes = [C.c_void_p, C.c_int32]
     L.wf_encoder_get_lanes.argtypes = [C.c_void_p]
+    L.wf_gemm_tile_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _ip, C.c_int32]
     L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
     L.wf_encoder_graph_stats.argtypes = [C.c_void_p, _lp, _lp, _lp]
@@ -571,3 +572,12 @@ def op_attention_noalloc(precision: int, qkv, out, cu_seqlens: Sequence[int], n_
     _check(lib().wf_op_attention_noalloc(precision, C.c_void_p(qkv.data_ptr()), C.c_void_p(out.data_ptr()), cu.ctypes.data_as(_ip),
                                          len(cu) - 1, n_heads, C.c_void_p(s)))
     return out
+
+
+def gemm_tile_map(M: int, N: int, tile_m: int = 256, tile_n: int = 256) -> np.ndarray:
+    """[n_units, 3] (first row, first column, width) of the GEMM's work units in workgroup order (host only)."""
+    cap = 2 * ((M + tile_m - 1) // tile_m) * (N // tile_n) + 8
+    units = np.zeros((cap, 3), dtype=np.int32)
+    n = lib().wf_gemm_tile_map(M, N, tile_m, tile_n, units.ctypes.data_as(_ip), cap)
+    _check(min(n, 0))
+    return units[:n]

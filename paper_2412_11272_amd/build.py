@@ -46,5 +46,33 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_sanitized_host_driver(driver_src: str, out_path: str) -> str:
+    """Every source of the library with AddressSanitizer + UndefinedBehaviorSanitizer on the HOST side (device
+    code is compiled as usual: GPU sanitizers are not used) and a driver program linked statically against those
+    objects.  For tests of the host logic (planning, validation, round bookkeeping, beam pruning); no GPU needed."""
+    obj_dir = os.path.join(OBJ_DIR, "asan")
+    os.makedirs(obj_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1"] + san
+    srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+
+    def comp(src, lang=()):
+        obj = os.path.join(obj_dir, os.path.basename(src) + ".o")
+        r = subprocess.run([HIPCC, *lang, *flags, "-c", src, "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed on {src}:\n{r.stderr}")
+        return obj
+
+    with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
+        futs = [ex.submit(comp, s) for s in srcs] + [ex.submit(comp, driver_src, ("-x", "hip"))]
+        objs = [f.result() for f in futs]
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+                        "-o", out_path, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link (sanitized) failed:\n" + r.stderr)
+    return out_path
+
+
 if __name__ == "__main__":
     build()

@@ -631,6 +631,14 @@ int wf_encoder_kernel_stats(wf_encoder *e, wf_kernel_stat *stats, int32_t n_stat
   return collect_stats(e, stats, n_stats);
 }
 
+int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32_t *units, int32_t capacity) {
+  if (!units || capacity < 0) return fail(WF_E_INVALID_ARG, "units is NULL or capacity negative");
+  if (M < 1 || N < 1 || tile_m < 1 || tile_n < 2 || tile_n % 2 || N % tile_n) return fail(WF_E_INVALID_ARG, "need M, N >= 1 and N a multiple of an even tile_n");
+  const int n = gemm_dl_tile_map(M, N, tile_m, tile_n, units, capacity);
+  if (n < 0) return fail(WF_E_CAPACITY, "more work units than capacity = %d", capacity);
+  return n;
+}
+
 // ---- operator-level entry points -------------------------------------------------------------
 int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const float *bias_dev, void *out_dev, int32_t M,
                  int32_t N, int32_t K, int32_t epilogue, void *hip_stream) {

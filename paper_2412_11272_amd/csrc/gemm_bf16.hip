@@ -568,35 +568,60 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 // them is split into two BM x BN/2 units so that the last round takes half as long (620 tiles on 256 CUs:
 // 2.5 rounds instead of 3).  Consecutive workgroup ids go to different XCDs; XCD x gets the full tiles at
 // positions [x*full_per_xcd, ...) of the order and the half units [x*half_per_xcd, ...), full tiles first.
+// Host and device share these two functions, so that the launcher's grid and the kernel's decoding of a workgroup id
+// cannot drift apart (and a host test can enumerate the units of any shape: every tile exactly once).
+struct DlUnit { int row, col, half; };   // tile row / column; half: 0 = whole tile, 1 / 2 = its left / right BN/2 columns
+
+// Split of tiles_m x tiles_n tiles over the chip; fills the work-unit fields of b and returns the grid size.
+__host__ inline int dl_plan(GemmArgs &b, int tiles_m, int tiles_n) {
+  constexpr int kCUs = 256;
+  const int tiles = tiles_m * tiles_n;
+  const int rest = tiles % kCUs;
+  const bool split = rest > 0 && 2 * rest <= kCUs;
+  b.n_full = split ? tiles - rest : tiles;
+  b.n_half = split ? 2 * rest : 0;
+  b.full_per_xcd = (b.n_full + 7) / 8;
+  b.half_per_xcd = (b.n_half + 7) / 8;
+  b.group_n = tiles_n >= 8 ? 4 : tiles_n;     // column groups only pay when a row of tiles is long
+  return 8 * (b.full_per_xcd + b.half_per_xcd);
+}
+
+// Workgroup id -> unit; false for the ids that round the grid up to whole groups of 8.
+__host__ __device__ inline bool dl_unit(const GemmArgs &p, int bid, int tiles_m, int tiles_n, DlUnit &u) {
+  // position t of the tile order -> (row, column): column groups of G tile columns, rows inside a group,
+  // columns inside a row (the last group may be narrower)
+  const int G = min(max(p.group_n, 1), tiles_n);
+  auto locate = [&](int t) {
+    const int gs = tiles_m * G;
+    const int g = t / gs, rem = t - g * gs;
+    const int gw = min(G, tiles_n - g * G);
+    u.row = rem / gw;
+    u.col = g * G + (rem - u.row * gw);
+  };
+  const int xcd = bid & 7, l = bid >> 3;
+  if (l < p.full_per_xcd) {
+    const int tile = xcd * p.full_per_xcd + l;
+    if (tile >= p.n_full) return false;
+    locate(tile);
+    u.half = 0;
+    return true;
+  }
+  const int hl = l - p.full_per_xcd;
+  const int h = xcd * p.half_per_xcd + hl;
+  if (hl >= p.half_per_xcd || h >= p.n_half) return false;
+  locate(p.n_full + (h >> 1));
+  u.half = 1 + (h & 1);
+  return true;
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, bool NT, int AMODE, int DEEP>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
   constexpr int SMEM = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tiles_n = p.N / BN, tiles_m = (p.M + BM - 1) / BM;
-  // position t of the tile order -> (row, column): column groups of G tile columns, rows inside a group,
-  // columns inside a row (the last group may be narrower)
-  const int G = min(max(p.group_n, 1), tiles_n);
-  auto locate = [&](int t, int &row, int &col) {
-    const int gs = tiles_m * G;
-    const int g = t / gs, rem = t - g * gs;
-    const int gw = min(G, tiles_n - g * G);
-    row = rem / gw;
-    col = g * G + (rem - row * gw);
-  };
-  const int xcd = blockIdx.x & 7, l = blockIdx.x >> 3;
-  int row, col;
-  if (l < p.full_per_xcd) {
-    const int tile = xcd * p.full_per_xcd + l;
-    if (tile >= p.n_full) return;
-    locate(tile, row, col);
-    dl_tile<BM, BN, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, row * BM, col * BN);
-  } else {
-    const int hl = l - p.full_per_xcd;
-    const int h = xcd * p.half_per_xcd + hl;
-    if (hl >= p.half_per_xcd || h >= p.n_half) return;
-    locate(p.n_full + (h >> 1), row, col);
-    dl_tile<BM, BN / 2, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, row * BM, col * BN + (h & 1) * (BN / 2));
-  }
+  DlUnit u;
+  if (!dl_unit(p, blockIdx.x, (p.M + BM - 1) / BM, p.N / BN, u)) return;
+  if (u.half == 0) dl_tile<BM, BN, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, u.row * BM, u.col * BN);
+  else dl_tile<BM, BN / 2, WM, WN, EPI, SMEM, NT, AMODE, DEEP>(p, smem, u.row * BM, u.col * BN + (u.half - 1) * (BN / 2));
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = A_PLAIN, int DEEP = 0>
@@ -607,17 +632,8 @@ hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   static hipError_t attr_err = hipSuccess;
   std::call_once(once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
   if (attr_err != hipSuccess) return attr_err;
-  const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   GemmArgs b = a;
-  constexpr int kCUs = 256;
-  const int rest = tiles % kCUs;
-  const bool split = rest > 0 && 2 * rest <= kCUs;
-  b.n_full = split ? tiles - rest : tiles;
-  b.n_half = split ? 2 * rest : 0;
-  b.full_per_xcd = (b.n_full + 7) / 8;
-  b.half_per_xcd = (b.n_half + 7) / 8;
-  b.group_n = a.N / BN >= 8 ? 4 : a.N / BN;     // column groups only pay when a row of tiles is long
-  const int grid = 8 * (b.full_per_xcd + b.half_per_xcd);
+  const int grid = dl_plan(b, (a.M + BM - 1) / BM, a.N / BN);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, b);
   return hipGetLastError();
 }
@@ -667,6 +683,26 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
                  : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+// Diagnostic: the work units the direct-load GEMM launches for an M x N result with bm x bn tiles, as
+// (first row, first column, width in columns) triples in workgroup order.  Returns the count, or -1 if cap is too small.
+int gemm_dl_tile_map(int32_t M, int32_t N, int32_t bm, int32_t bn, int32_t *units, int32_t cap) {
+  GemmArgs b{};
+  b.M = M; b.N = N;
+  const int tiles_m = (M + bm - 1) / bm, tiles_n = N / bn;
+  const int grid = dl_plan(b, tiles_m, tiles_n);
+  int n = 0;
+  for (int bid = 0; bid < grid; ++bid) {
+    DlUnit u;
+    if (!dl_unit(b, bid, tiles_m, tiles_n, u)) continue;
+    if (n >= cap) return -1;
+    units[3 * n] = u.row * bm;
+    units[3 * n + 1] = u.col * bn + (u.half == 2 ? bn / 2 : 0);
+    units[3 * n + 2] = u.half == 0 ? bn : bn / 2;
+    ++n;
+  }
+  return n;
 }
 
 }  // namespace wf

@@ -106,3 +106,22 @@ def test_workload_recipes():
     assert abs(w["layers"][0]["wq"].std() - 0.02) < 1e-3 and w["layers"][0]["bk"] is None
     w4, h4, m4 = synth.materialize(synth.workload("cfg4a"))
     assert m4[0].shape == (3000, 80) and np.all(m4[0][600:] == -1.0) and len(h4) == 0
+
+
+@pytest.mark.parametrize("M,N,tm,tn", [(31694, 3840, 256, 256), (31694, 5120, 256, 256), (31694, 1280, 256, 256), (15847, 3840, 256, 256),
+                                       (12000, 4096, 256, 256), (6400, 1280, 128, 128), (75, 384, 128, 128), (1, 128, 128, 128),
+                                       (65536, 2560, 256, 256), (257, 256, 256, 256), (63408, 1280, 256, 256)])
+def test_gemm_work_units_cover_every_tile_exactly_once(M, N, tm, tn):
+    """The workgroup -> tile decoding the GEMM kernel runs (XCD striping, column groups, half-width units for the
+    last partial round), enumerated on the host: every column block of every tile row exactly once."""
+    units = wf.gemm_tile_map(M, N, tm, tn)
+    tiles_m = (M + tm - 1) // tm
+    cover = np.zeros((tiles_m, N // (tn // 2)), dtype=np.int32)       # in half-tile columns
+    for m0, n0, w in units:
+        assert m0 % tm == 0 and 0 <= m0 < tiles_m * tm and n0 % (tn // 2) == 0 and w in (tn, tn // 2) and n0 + w <= N
+        if w == tn:
+            assert n0 % tn == 0
+        cover[m0 // tm, n0 // (tn // 2):(n0 + w) // (tn // 2)] += 1
+    assert cover.min() == 1 and cover.max() == 1
+    full = int((units[:, 2] == tn).sum())
+    assert full % 256 == 0 or len(units) == full                     # halves only after whole rounds of the chip
