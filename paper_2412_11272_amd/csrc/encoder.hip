@@ -403,12 +403,18 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     char *qkv = (char *)e->qkv + (size_t)r0 * 3 * d * es;
     char *hbuf = (char *)e->h + (size_t)h_row0 * f * es;           // panel-aligned start of this lane's hidden activations
     const int panels = e->bf16 ? 1 : 0;                            // the fp32 debug kernels keep everything row-major
+    // A group of at most about a thousand tokens runs on the small-batch GEMM (all of its products, so that a row's
+    // arithmetic does not depend on which other streams share the batch), which also normalises its activation
+    // operand itself: the two LayerNorm launches of a block disappear and the MLP's hidden activations stay row-major.
+    const bool small = e->bf16 && gemm_small_applies(Mg);
+    const int hpanels = small ? 0 : panels;
     int rc;
     {   // a1: conv1 + GELU as a GEMM over 3-frame windows (row maps hold absolute rows of the packed input)
       GemmArgs a{};
       a.A = e->packed; a.W = e->conv1_w; a.bias = e->conv1_b; a.out = G;
       a.M = Fg; a.N = d; a.K = e->k1p; a.lda = C; a.ldo = d;
       a.row_src = e->frame_src + f0; a.row_flags = e->frame_flags + f0; a.C = C;
+      a.prefer_small = small;
       if ((rc = run_gemm(e, ls, KC_CONV1, a, A_CONV3, EPI_BIAS_GELU, 3 * C, (int)es, Fg, C))) return rc;
     }
     {   // a2: conv2 (stride 2) + GELU + positions -> fp32 residual stream
@@ -426,12 +432,13 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
     }
     for (int l = 0; l < c.n_layers; ++l) {
       const LayerDev &w = e->layers[l];
-      if ((rc = run_ln(e, ls, KC_LN, x, w.ln1_g, w.ln1_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
+      if (!small && (rc = run_ln(e, ls, KC_LN, x, w.ln1_g, w.ln1_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
       {
         GemmArgs a{};
         a.A = u; a.W = w.wqkv; a.bias = w.bqkv; a.out = qkv; a.M = Mg; a.N = 3 * d; a.K = d; a.lda = d; a.ldo = 3 * d;
         a.w_panels = panels;
-        if ((rc = run_gemm(e, ls, KC_QKV, a, A_PLAIN, EPI_BIAS, d, (int)es, Mg, d))) return rc;
+        if (small) { a.A = x; a.ln_g = w.ln1_g; a.ln_b = w.ln1_b; a.ln_eps = c.ln_eps; }
+        if ((rc = run_gemm(e, ls, KC_QKV, a, small ? A_LN : A_PLAIN, EPI_BIAS, d, (int)es, Mg, d))) return rc;
       }
       {
         AttnArgs a{};   // q, k, v and out are addressed through the absolute prefix sums, so the bases stay whole-batch
@@ -449,18 +456,19 @@ int wf_encode_batch(wf_encoder *e, const void *mel_dev, int32_t mel_dtype, const
         a.w_panels = panels;
         if ((rc = run_gemm(e, ls, KC_OUT, a, A_PLAIN, EPI_BIAS_RESID, d, 4, Mg, d))) return rc;
       }
-      if ((rc = run_ln(e, ls, KC_LN, x, w.ln2_g, w.ln2_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
+      if (!small && (rc = run_ln(e, ls, KC_LN, x, w.ln2_g, w.ln2_b, u, act_bf16, Mg, d, c.ln_eps))) return rc;
       {   // fc1 writes the hidden activations as [rows/256][f/64][256][64] panels: one contiguous 32 KB block per
           // K step of fc2's activation operand (whose rows would otherwise be 2 f bytes apart in memory)
         GemmArgs a{};
         a.A = u; a.W = w.w1; a.bias = w.b1; a.out = hbuf; a.M = Mg; a.N = f; a.K = d; a.lda = d; a.ldo = f;
-        a.out_panels = panels; a.w_panels = panels;
-        if ((rc = run_gemm(e, ls, KC_FC1, a, A_PLAIN, EPI_BIAS_GELU, d, (int)es, Mg, d))) return rc;
+        a.out_panels = hpanels; a.w_panels = panels;
+        if (small) { a.A = x; a.ln_g = w.ln2_g; a.ln_b = w.ln2_b; a.ln_eps = c.ln_eps; }
+        if ((rc = run_gemm(e, ls, KC_FC1, a, small ? A_LN : A_PLAIN, EPI_BIAS_GELU, d, (int)es, Mg, d))) return rc;
       }
       {
         GemmArgs a{};
         a.A = hbuf; a.W = w.w2; a.bias = w.b2; a.out = x; a.M = Mg; a.N = d; a.K = f; a.lda = f; a.ldo = d;
-        a.a_panels = panels; a.w_panels = panels;
+        a.a_panels = hpanels; a.w_panels = panels;
         if ((rc = run_gemm(e, ls, KC_FC2, a, A_PLAIN, EPI_BIAS_RESID, f, 4, Mg, f))) return rc;
       }
     }

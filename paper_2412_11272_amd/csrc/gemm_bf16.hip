@@ -647,6 +647,8 @@ bool use_large_tile(const GemmArgs &a) {
 
 hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
+  if ((gemm_small_applies(a.M) || a.prefer_small) && !a.a_panels && !a.out_panels) return launch_gemm_small(a, amode, epi, s);
+  if (amode == A_LN) return hipErrorInvalidValue;      // the fused LayerNorm operand exists in the small-batch kernel only
   if (a.N % 128 != 0 || a.K % BK != 0 || a.K <= 0) return hipErrorInvalidValue;
   const bool big = use_large_tile(a);
   if (amode == A_PLAIN) {

@@ -15,6 +15,8 @@ enum AMode : int {
   A_CONV3 = 1,   // row r is a contiguous window of 3*C elements starting at row_src[r] * C of a
                  // [rows, C] matrix: the three taps of a width-3 convolution.  row_flags[r] bit 0
                  // zeroes tap 0 (first frame of a stream), bit 1 zeroes tap 2 (last frame).
+  A_LN = 2,      // small-batch kernel only: A is an fp32 matrix x (row stride lda) and the operand is LayerNorm(x) with
+                 // ln_g / ln_b / ln_eps, normalised on the way in
 };
 
 // What the GEMM does with acc = A . W^T.
@@ -48,6 +50,11 @@ struct GemmArgs {
   // EPI_BIAS_GELU_POS only
   const float *pos;         // [n_pos, N]
   const int32_t *row_pos;   // [M]
+  // A_LN only
+  const float *ln_g, *ln_b; // [K]
+  float ln_eps;
+  int32_t prefer_small;     // run on the small-batch kernel even if M is above its usual limit (the first convolution
+                            // of a small batch has twice as many rows as the batch has tokens)
 };
 
 struct AttnArgs {
@@ -77,6 +84,9 @@ struct PrepArgs {
 
 // bf16 MFMA path -------------------------------------------------------------------------------
 hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);
+// small row counts (gemm_small_applies(M)): 32 x 32 tiles, reduction split over the waves, optional fused LayerNorm
+bool gemm_small_applies(int32_t M);
+hipError_t launch_gemm_small(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);
 hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 hipError_t launch_layernorm(const float *x, const float *g, const float *b, void *out, int out_bf16,
                             int32_t M, int32_t d, float eps, hipStream_t s);

@@ -92,6 +92,8 @@ def test_ragged_equals_per_stream_and_padded_layout_and_reuse():
             assert cu1.tolist() == [0, cu[i + 1] - cu[i]]
             assert H.rel_err(one, ref[cu[i]:cu[i + 1]]) <= H.BF16_TOL
             # same arithmetic per row whatever the batch: GEMM rows and attention are independent of neighbours
+            # (both batches are small enough for the small-batch kernels; a batch of more than about a thousand
+            # tokens runs on other kernels, whose results differ from these at the level of bf16 rounding)
             np.testing.assert_allclose(one, full[cu[i]:cu[i + 1]], atol=1e-5)
         order = [5, 2, 0, 1, 4, 3]
         flat2, offs2, nf2 = wf.pack_mels([mels[i] for i in order])
@@ -174,9 +176,12 @@ def test_kernel_stats_cover_every_launch():
         enc.encode(mel, offs, nf)
         st = {s["name"]: s for s in enc.kernel_stats()}
         n = wl.shape.n_layers
-        assert st["gemm_qkv"]["launches"] == n and st["attention"]["launches"] == n and st["layernorm"]["launches"] == 2 * n
+        assert st["gemm_qkv"]["launches"] == n and st["attention"]["launches"] == n
+        # a batch this small (868 tokens) normalises inside the QKV and fc1 kernels: no LayerNorm launches in the blocks
+        assert st["layernorm"]["launches"] == 0
         assert st["prep_pack_hush"]["launches"] == 1 and st["layernorm_final"]["launches"] == 1
-        assert all(s["total_ms"] > 0 for s in st.values())
+        assert sum(s["launches"] for s in st.values()) == 4 + 5 * n
+        assert all(s["total_ms"] > 0 for s in st.values() if s["launches"])
         enc.set_profiling(False)
         enc.encode(mel, offs, nf)
         assert sum(s["launches"] for s in enc.kernel_stats()) == 0
