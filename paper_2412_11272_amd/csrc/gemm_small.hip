@@ -5,12 +5,14 @@
 //   out = epilogue(A . W^T),  A [M, K], W [N, K], fp32 accumulation, M up to about a thousand rows.
 //
 // Differences from the large-batch kernels of gemm_bf16.hip:
-//   * 32 x 32 output tiles, so that even a 75-token batch spreads over dozens of compute units
-//     (75 x 384: 36 workgroups instead of 3);
+//   * 32-row output tiles, 32, 64 or 128 columns wide (NB column blocks of 32), so that even a 75-token batch spreads
+//     over dozens of compute units (75 x 384: 36 workgroups instead of 3); the launcher takes the widest tile that
+//     still leaves about 128 workgroups, because every column tile re-reads (and with A_LN re-normalises) the same
+//     32 activation rows;
 //   * the four waves of a workgroup split the reduction: in every 64-deep K step wave w multiplies the k slice
 //     [16 w, 16 w + 16) with one 32x32x16 MFMA, and the four partial tiles are added in a fixed order through LDS
 //     at the end (deterministic);
-//   * operand chunks are requested four K steps ahead into registers, so the K loop runs at the rate the chunks
+//   * operand chunks are requested eight (widest tile: four) K steps ahead into registers, so the K loop runs at the rate the chunks
 //     arrive instead of one memory latency per step;
 //   * A_LN: the activation operand is LayerNorm(x) of an fp32 matrix x, normalised on the way into LDS.  The
 //     workgroup first computes mean and 1/sqrt(var + eps) of its 32 rows (one pass, sums shifted by the row's first
@@ -27,16 +29,20 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int SBM = 32, SBN = 32, SBK = 64, DEPTH = 4;
+constexpr int SBM = 32, SBN = 32, SBK = 64;
+constexpr int kMaxLnK = 2048;     // A_LN keeps the LayerNorm gain and shift of the whole row in LDS
 
-template <int AMODE, int EPI>
+template <int AMODE, int EPI, int NB>
 __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
+  constexpr int TN = NB * SBN;                                               // tile width in columns
+  constexpr int DEPTH = NB >= 4 ? 4 : 8;                                     // K steps in flight (register ring)
   __shared__ __attribute__((aligned(16))) unsigned char sA[2][SBM * 128];   // [stage][row][64 bf16]
-  __shared__ __attribute__((aligned(16))) unsigned char sW[2][SBN * 128];
-  __shared__ __attribute__((aligned(16))) float sPart[4][SBM][SBN + 4];      // the four waves' partial tiles
+  __shared__ __attribute__((aligned(16))) unsigned char sW[2][TN * 128];
+  __shared__ __attribute__((aligned(16))) float sPart[4][SBM][TN + 4];       // the four waves' partial tiles
+  __shared__ __attribute__((aligned(16))) float sGain[AMODE == A_LN ? kMaxLnK : 4], sShift[AMODE == A_LN ? kMaxLnK : 4];
 
-  const int tiles_n = p.N / SBN;
-  const int m0 = (blockIdx.x / tiles_n) * SBM, n0 = (blockIdx.x % tiles_n) * SBN;
+  const int tiles_n = p.N / TN;
+  const int m0 = (blockIdx.x / tiles_n) * SBM, n0 = (blockIdx.x % tiles_n) * TN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lg = lane >> 5;
 
@@ -46,8 +52,12 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
   row = row < p.M ? row : p.M - 1;               // rows past M are computed but never stored
   const int lds_off = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   const __bf16 *W = (const __bf16 *)p.W;
-  const int n = n0 + r;
-  const __bf16 *wptr = p.w_panels ? W + ((size_t)(n >> 8) * (p.K >> 6) << 14) + ((n & 255) << 6) + ch * 8 : W + (size_t)n * p.K + ch * 8;
+  const __bf16 *wptr[NB];                        // weight rows n0 + 32 j + r
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int n = n0 + j * SBN + r;
+    wptr[j] = p.w_panels ? W + ((size_t)(n >> 8) * (p.K >> 6) << 14) + ((n & 255) << 6) + ch * 8 : W + (size_t)n * p.K + ch * 8;
+  }
   const int wstep = p.w_panels ? 1 << 14 : SBK;
   const __bf16 *aptr = nullptr;
   const float *xptr = nullptr;
@@ -58,40 +68,15 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
     flags = p.row_flags[row];
   } else xptr = (const float *)p.A + (size_t)row * p.lda + ch * 8;
 
-  // ---- A_LN: statistics of the tile's 32 rows.  Eight threads per row, each over every eighth 32-byte piece.
-  [[maybe_unused]] float mu = 0.0f, rstd = 0.0f;
-  if constexpr (AMODE == A_LN) {
-    const float *xr = (const float *)p.A + (size_t)row * p.lda;
-    const float pivot = xr[0];
-    float s1 = 0.0f, s2 = 0.0f;
-    for (int k = ch * 8; k < p.K; k += 64) {
-      const f32x4 a = *(const f32x4 *)(xr + k), b = *(const f32x4 *)(xr + k + 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float da = a[e] - pivot, db = b[e] - pivot;
-        s1 += da + db;
-        s2 += da * da + db * db;
-      }
-    }
-#pragma unroll
-    for (int off = 4; off > 0; off >>= 1) {     // the eight threads of a row are neighbouring lanes
-      s1 += __shfl_xor(s1, off);
-      s2 += __shfl_xor(s2, off);
-    }
-    const float inv_k = 1.0f / (float)p.K;
-    const float ms = s1 * inv_k;                 // mean - pivot
-    const float var = fmaxf(s2 * inv_k - ms * ms, 0.0f);
-    mu = pivot + ms;
-    rstd = rsqrtf(var + p.ln_eps);
-  }
-
+  [[maybe_unused]] float mu = 0.0f, rstd = 0.0f;     // A_LN: statistics of this thread's row
   // ---- operand pipeline: chunks of K step kt + DEPTH - 1 are requested while step kt is multiplied
-  u32x4 wreg[DEPTH];
+  u32x4 wreg[DEPTH][NB];
   [[maybe_unused]] u32x4 areg[DEPTH];
   [[maybe_unused]] f32x4 xreg[DEPTH][2];
   const int nk = p.K / SBK;
   auto request = [&](int kt, int slot) {
-    wreg[slot] = *(const u32x4 *)(wptr + (size_t)kt * wstep);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) wreg[slot][j] = *(const u32x4 *)(wptr[j] + (size_t)kt * wstep);
     if constexpr (AMODE == A_PLAIN) {
       areg[slot] = *(const u32x4 *)(aptr + kt * SBK);
     } else if constexpr (AMODE == A_CONV3) {
@@ -108,11 +93,12 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
   };
   auto commit = [&](int kt, int slot) {          // registers -> LDS stage kt & 1
     unsigned char *dA = sA[kt & 1] + lds_off, *dW = sW[kt & 1] + lds_off;
-    *(u32x4 *)dW = wreg[slot];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) *(u32x4 *)(dW + j * SBN * 128) = wreg[slot][j];
     if constexpr (AMODE == A_LN) {
       const int k = kt * SBK + ch * 8;
-      const f32x4 g0 = *(const f32x4 *)(p.ln_g + k), g1 = *(const f32x4 *)(p.ln_g + k + 4);
-      const f32x4 b0 = *(const f32x4 *)(p.ln_b + k), b1 = *(const f32x4 *)(p.ln_b + k + 4);
+      const f32x4 g0 = *(const f32x4 *)&sGain[k], g1 = *(const f32x4 *)&sGain[k + 4];
+      const f32x4 b0 = *(const f32x4 *)&sShift[k], b1 = *(const f32x4 *)&sShift[k + 4];
       f32x4 y0, y1;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -126,12 +112,56 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
     }
   };
 
-  f32x16 acc;
+  f32x16 acc[NB];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.0f;
 #pragma unroll
   for (int d = 0; d < DEPTH - 1; ++d)
     if (d < nk) request(d, d);
+  // ---- A_LN: statistics of the tile's 32 rows (after the first operand requests, so that their latencies overlap).
+  // Eight threads per row, each over every eighth 32-byte piece, eight pieces requested at a time.
+  if constexpr (AMODE == A_LN) {
+    for (int k = tid * 4; k < p.K; k += 1024) {   // gain and shift of the whole row -> LDS (a load per K step would sit
+      *(f32x4 *)&sGain[k] = *(const f32x4 *)(p.ln_g + k);   // on the critical path of every step)
+      *(f32x4 *)&sShift[k] = *(const f32x4 *)(p.ln_b + k);
+    }
+    const float *xr = (const float *)p.A + (size_t)row * p.lda;
+    const float pivot = xr[0];
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int k0 = ch * 8; k0 < p.K; k0 += 512) {
+      f32x4 a[8], b[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int k = min(k0 + i * 64, p.K - 8);         // past the end: a valid address, the values are not used
+        a[i] = *(const f32x4 *)(xr + k);
+        b[i] = *(const f32x4 *)(xr + k + 4);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (k0 + i * 64 < p.K) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float da = a[i][e] - pivot, db = b[i][e] - pivot;
+            s1 += da + db;
+            s2 += da * da + db * db;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {     // the eight threads of a row are neighbouring lanes
+      s1 += __shfl_xor(s1, off);
+      s2 += __shfl_xor(s2, off);
+    }
+    const float inv_k = 1.0f / (float)p.K;
+    const float ms = s1 * inv_k;                 // mean - pivot
+    const float var = fmaxf(s2 * inv_k - ms * ms, 0.0f);
+    mu = pivot + ms;
+    rstd = rsqrtf(var + p.ln_eps);
+    __syncthreads();                             // gain / shift are in LDS
+  }
   // fragment of wave `wave`: row l32, k slice 16 * wave + 8 * lg .. + 7 = chunk 2 * wave + lg
   const int frag_off = l32 * 128 + (((2 * wave + lg) ^ ((l32 >> 1) & 7)) << 4);
   for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
@@ -142,57 +172,79 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
         commit(kt, d);
         if (kt + DEPTH - 1 < nk) request(kt + DEPTH - 1, (d + DEPTH - 1) % DEPTH);
         __syncthreads();                         // stage kt & 1 is complete; stage (kt + 1) & 1 is no longer read
-        const bf16x8 wf = *(const bf16x8 *)(sW[kt & 1] + frag_off);
         const bf16x8 xf = *(const bf16x8 *)(sA[kt & 1] + frag_off);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const bf16x8 wf = *(const bf16x8 *)(sW[kt & 1] + j * SBN * 128 + frag_off);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[j], 0, 0, 0);
+        }
       }
     }
   }
 
-  // ---- the four k slices are added in wave order; lane holds token l32, features 8 (i / 4) + 4 lg + i % 4
+  // ---- the four k slices are added in wave order; lane holds token l32, features 8 (i / 4) + 4 lg + i % 4 of block j
 #pragma unroll
-  for (int i = 0; i < 16; ++i) sPart[wave][l32][8 * (i >> 2) + 4 * lg + (i & 3)] = acc[i];
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sPart[wave][l32][j * SBN + 8 * (i >> 2) + 4 * lg + (i & 3)] = acc[j][i];
   __syncthreads();
-  const int er = tid >> 3, ec = (tid & 7) * 4;   // thread -> row er, 4 consecutive features from ec
-  f32x4 v = *(const f32x4 *)&sPart[0][er][ec];
-#pragma unroll
-  for (int w = 1; w < 4; ++w) {
-    const f32x4 t = *(const f32x4 *)&sPart[w][er][ec];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += t[e];
-  }
-  const int m = m0 + er;
+  // thread -> row er, 4 consecutive features from ec in each of the NB column blocks
+  const int er = tid >> 3, m = m0 + er;
   if (m >= p.M) return;
-  const int nn = n0 + ec;
-  const f32x4 b = *(const f32x4 *)(p.bias + nn);
+  [[maybe_unused]] int prow = 0;
+  if constexpr (EPI == EPI_BIAS_GELU_POS) prow = p.row_pos[m];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) v[e] += b[e];
-  if constexpr (EPI == EPI_BIAS) {
-    *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nn) = to_bf16x4(v);
-  } else if constexpr (EPI == EPI_BIAS_GELU) {
+  for (int j = 0; j < NB; ++j) {
+    const int ec = j * SBN + (tid & 7) * 4;
+    f32x4 v = *(const f32x4 *)&sPart[0][er][ec];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
-    *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nn) = to_bf16x4(v);
-  } else if constexpr (EPI == EPI_BIAS_RESID) {
-    f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn);
-    const f32x4 x = *o;
+    for (int w = 1; w < 4; ++w) {
+      const f32x4 t = *(const f32x4 *)&sPart[w][er][ec];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += x[e];
-    *o = v;
-  } else if constexpr (EPI == EPI_BIAS_F32) {
-    *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn) = v;
-  } else {
-    const f32x4 pe = *(const f32x4 *)(p.pos + (size_t)p.row_pos[m] * p.N + nn);
+      for (int e = 0; e < 4; ++e) v[e] += t[e];
+    }
+    const int nn = n0 + ec;
+    const f32x4 b = *(const f32x4 *)(p.bias + nn);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]) + pe[e];
-    *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn) = v;
+    for (int e = 0; e < 4; ++e) v[e] += b[e];
+    if constexpr (EPI == EPI_BIAS) {
+      *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nn) = to_bf16x4(v);
+    } else if constexpr (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
+      *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nn) = to_bf16x4(v);
+    } else if constexpr (EPI == EPI_BIAS_RESID) {
+      f32x4 *o = (f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn);
+      const f32x4 x = *o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += x[e];
+      *o = v;
+    } else if constexpr (EPI == EPI_BIAS_F32) {
+      *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn) = v;
+    } else {
+      const f32x4 pe = *(const f32x4 *)(p.pos + (size_t)prow * p.N + nn);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]) + pe[e];
+      *(f32x4 *)((float *)p.out + (size_t)m * p.ldo + nn) = v;
+    }
   }
+}
+
+// Widest tile (in 32-column blocks) that divides N and still leaves about 128 workgroups; 1 if even that gives fewer.
+int pick_blocks(const GemmArgs &a) {
+  const long rows = (a.M + SBM - 1) / SBM;
+  for (int nb = 4; nb > 1; nb >>= 1)
+    if (a.N % (nb * SBN) == 0 && rows * (a.N / (nb * SBN)) >= 128) return nb;
+  return 1;
 }
 
 template <int AMODE, int EPI>
 hipError_t launch_small(const GemmArgs &a, hipStream_t s) {
-  const long tiles = (long)((a.M + SBM - 1) / SBM) * (a.N / SBN);
-  hipLaunchKernelGGL((gemm_small_kernel<AMODE, EPI>), dim3((unsigned)tiles), dim3(256), 0, s, a);
+  const int nb = pick_blocks(a);
+  const dim3 grid((unsigned)((long)((a.M + SBM - 1) / SBM) * (a.N / (nb * SBN)))), block(256);
+  if (nb == 4) hipLaunchKernelGGL((gemm_small_kernel<AMODE, EPI, 4>), grid, block, 0, s, a);
+  else if (nb == 2) hipLaunchKernelGGL((gemm_small_kernel<AMODE, EPI, 2>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((gemm_small_kernel<AMODE, EPI, 1>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -214,7 +266,7 @@ hipError_t launch_gemm_small(const GemmArgs &a, AMode amode, Epilogue epi, hipSt
     }
   }
   if (amode == A_LN) {
-    if (a.lda % 8 != 0 || !a.ln_g || !a.ln_b || !(a.ln_eps > 0.0f)) return hipErrorInvalidValue;
+    if (a.lda % 8 != 0 || !a.ln_g || !a.ln_b || !(a.ln_eps > 0.0f) || a.K > kMaxLnK) return hipErrorInvalidValue;
     switch (epi) {
       case EPI_BIAS: return launch_small<A_LN, EPI_BIAS>(a, s);
       case EPI_BIAS_GELU: return launch_small<A_LN, EPI_BIAS_GELU>(a, s);
