@@ -14,11 +14,11 @@ using namespace wf::host;
 namespace {
 
 enum DClass : int {
-  DC_CROSS_KV = 0, DC_EMBED, DC_LN, DC_SELF_Q, DC_SELF_KV, DC_SELF_ATTN, DC_SELF_OUT, DC_CROSS_Q, DC_CROSS_ATTN,
+  DC_CROSS_KV = 0, DC_EMBED, DC_LN, DC_SELF_Q, DC_SELF_KV, DC_SELF_QKV, DC_SELF_ATTN, DC_SELF_OUT, DC_CROSS_Q, DC_CROSS_ATTN,
   DC_CROSS_OUT, DC_FC1, DC_FC2, DC_LNF, DC_LOGITS, DC_COUNT
 };
 const char *const kDecClassNames[DC_COUNT] = {
-    "cross_kv_gemm", "embed", "layernorm", "gemm_self_q", "gemm_self_kv", "attention_causal", "gemm_self_out_resid",
+    "cross_kv_gemm", "embed", "layernorm", "gemm_self_q", "gemm_self_kv", "gemm_self_qkv", "attention_causal", "gemm_self_out_resid",
     "gemm_cross_q", "attention_cross", "gemm_cross_out_resid", "gemm_fc1_gelu", "gemm_fc2_resid", "layernorm_final",
     "gemm_logits"};
 
@@ -26,6 +26,8 @@ struct DecLayerDev {
   float *ln1_g, *ln1_b, *lnx_g, *lnx_b, *ln2_g, *ln2_b;
   void *wq, *wkv, *wo, *xwq, *xwkv, *xwo, *w1, *w2;     // act dtype; wkv / xwkv = [2d, d]: key rows then value rows
   float *bq, *bkv, *bo, *xbq, *xbkv, *xbo, *b1, *b2;    // bkv / xbkv = 0 | bv
+  void *wqkv;                                           // bf16 path: [3d, d] = wq | wk | wv rows, one product for q, k and v
+  float *bqkv;                                          //            bq | 0 | bv
 };
 
 }  // namespace
@@ -104,8 +106,20 @@ int dec_create_impl(wf_decoder *e, const wf_decoder_config *cfg, const wf_decode
                           s.xwv, s.xbv, s.xwo, s.xbo, s.ln2_g, s.ln2_b, s.w1, s.b1, s.w2, s.b2};
     for (const float *p : req)
       if (!p) return fail(WF_E_INVALID_ARG, "decoder layer %d: a weight pointer is NULL", l);
-    if ((rc = upload_w(e, &t.wq, s.wq, d * d)) || (rc = upload_f32(e, &t.bq, s.bq, d))) return rc;
-    if ((rc = upload_kv(e, &t.wkv, &t.bkv, s.wk, s.wv, s.bv))) return rc;
+    t.wq = t.wkv = t.wqkv = nullptr;
+    t.bq = t.bkv = t.bqkv = nullptr;
+    if (!e->bf16) {
+      if ((rc = upload_w(e, &t.wq, s.wq, d * d)) || (rc = upload_f32(e, &t.bq, s.bq, d))) return rc;
+      if ((rc = upload_kv(e, &t.wkv, &t.bkv, s.wk, s.wv, s.bv))) return rc;
+    } else {
+      std::vector<float> wf(3 * d * d), bf(3 * d, 0.0f);
+      memcpy(wf.data(), s.wq, d * d * 4);
+      memcpy(wf.data() + d * d, s.wk, d * d * 4);
+      memcpy(wf.data() + 2 * d * d, s.wv, d * d * 4);
+      memcpy(bf.data(), s.bq, d * 4);
+      memcpy(bf.data() + 2 * d, s.bv, d * 4);
+      if ((rc = upload_w(e, &t.wqkv, wf)) || (rc = upload_f32(e, &t.bqkv, bf.data(), bf.size()))) return rc;
+    }
     if ((rc = upload_w(e, &t.wo, s.wo, d * d)) || (rc = upload_f32(e, &t.bo, s.bo, d))) return rc;
     if ((rc = upload_w(e, &t.xwq, s.xwq, d * d)) || (rc = upload_f32(e, &t.xbq, s.xbq, d))) return rc;
     if ((rc = upload_kv(e, &t.xwkv, &t.xbkv, s.xwk, s.xwv, s.xbv))) return rc;
@@ -271,8 +285,15 @@ int wf_prefill(wf_decoder *e, const int32_t *tokens, const int32_t *cu_prompt, c
     const char *xkv = (const char *)cross_kv_dev + (size_t)l * kv_capacity_tokens * 2 * d * es;
     // causal self-attention among the prompt tokens
     if ((rc = run_ln(e, s, DC_LN, e->x, w.ln1_g, w.ln1_b, e->u, act_bf16, Pt, d, c.ln_eps))) return rc;
-    if ((rc = run_linear(e, s, DC_SELF_Q, e->u, d, w.wq, w.bq, e->qbuf, d, Pt, d, d, EPI_BIAS))) return rc;
-    if ((rc = run_linear(e, s, DC_SELF_KV, e->u, d, w.wkv, w.bkv, skv, 2 * d, Pt, 2 * d, d, EPI_BIAS))) return rc;
+    if (e->bf16) {     // one product for q | k | v: the first d result columns go to the query buffer, the rest to the K/V cache
+      GemmArgs a{};
+      a.A = e->u; a.W = w.wqkv; a.bias = w.bqkv; a.out = e->qbuf; a.M = Pt; a.N = 3 * d; a.K = d; a.lda = d; a.ldo = d;
+      a.out2 = skv; a.n_split = d; a.ldo2 = 2 * d;
+      if ((rc = run_gemm(e, s, DC_SELF_QKV, a, A_PLAIN, EPI_BIAS, d, (int)es, Pt, d))) return rc;
+    } else {
+      if ((rc = run_linear(e, s, DC_SELF_Q, e->u, d, w.wq, w.bq, e->qbuf, d, Pt, d, d, EPI_BIAS))) return rc;
+      if ((rc = run_linear(e, s, DC_SELF_KV, e->u, d, w.wkv, w.bkv, skv, 2 * d, Pt, 2 * d, d, EPI_BIAS))) return rc;
+    }
     {
       AttnArgs a{};
       a.q = e->qbuf; a.ldq = d; a.k = skv; a.v = skv + (size_t)d * es; a.ldkv = 2 * d; a.out = e->u;
@@ -304,9 +325,16 @@ int wf_prefill(wf_decoder *e, const int32_t *tokens, const int32_t *cu_prompt, c
   if (logits_out_dev) {
     hipError_t err = launch_gather_rows(e->u, d_last, e->ulast, B, (int)(d * es), s);
     if (err != hipSuccess) return fail(WF_E_HIP, "gather launch: %s", hipGetErrorString(err));
-    if ((rc = run_linear(e, s, DC_LOGITS, e->ulast, d, e->tok_emb, e->zero_bias, e->lbuf, e->vpad, B, e->vpad, d, EPI_BIAS_F32))) return rc;
-    WF_HIP_TRY(hipMemcpy2DAsync(logits_out_dev, (size_t)c.n_vocab * 4, e->lbuf, (size_t)e->vpad * 4, (size_t)c.n_vocab * 4, B,
-                                hipMemcpyDeviceToDevice, s));
+    // (the weight-streaming logits product keeps the 128-wide tile even for a handful of rows: measured 46 us against
+    // 63 us on the small-batch kernel for 64 x 51866 x 1280)
+    {
+      GemmArgs a{};
+      a.A = e->ulast; a.W = e->tok_emb; a.bias = e->zero_bias; a.out = e->lbuf; a.M = B; a.N = e->vpad; a.K = d; a.lda = d; a.ldo = e->vpad;
+      a.prefer_large = 1;
+      if ((rc = run_gemm(e, s, DC_LOGITS, a, A_PLAIN, EPI_BIAS_F32, d, 4, B, d))) return rc;
+      WF_HIP_TRY(hipMemcpy2DAsync(logits_out_dev, (size_t)c.n_vocab * 4, e->lbuf, (size_t)e->vpad * 4, (size_t)c.n_vocab * 4, B,
+                                  hipMemcpyDeviceToDevice, s));
+    }
   }
   return WF_OK;
 }

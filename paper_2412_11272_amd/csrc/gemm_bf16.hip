@@ -485,7 +485,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       if (m < p.M) {
         const int n = nw0 + c * 8;
         __bf16 *dst = p.out_panels ? (__bf16 *)p.out + ((((size_t)(m >> 8) * (p.N >> 6) + (n >> 6)) << 14) + ((m & 255) << 6) + (n & 63))
-                                   : (__bf16 *)p.out + (size_t)m * p.ldo + n;
+                      : (p.out2 && n >= p.n_split) ? (__bf16 *)p.out2 + (size_t)m * p.ldo2 + (n - p.n_split)
+                                                   : (__bf16 *)p.out + (size_t)m * p.ldo + n;
         // Large bf16 results (QKV, the MLP's hidden activations) are written with the non-temporal hint:
         // they are far bigger than what the caches can hand to the consumer, and written plainly they
         // push the residual stream and the operands of the next kernels out of the memory-side cache.
@@ -647,13 +648,14 @@ bool use_large_tile(const GemmArgs &a) {
 
 hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
-  if ((gemm_small_applies(a.M) || a.prefer_small) && !a.a_panels && !a.out_panels) return launch_gemm_small(a, amode, epi, s);
+  if ((gemm_small_applies(a.M) || a.prefer_small) && !a.prefer_large && !a.a_panels && !a.out_panels) return launch_gemm_small(a, amode, epi, s);
   if (amode == A_LN) return hipErrorInvalidValue;      // the fused LayerNorm operand exists in the small-batch kernel only
   if (a.N % 128 != 0 || a.K % BK != 0 || a.K <= 0) return hipErrorInvalidValue;
   const bool big = use_large_tile(a);
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
     if (a.out_panels && epi != EPI_BIAS && epi != EPI_BIAS_GELU) return hipErrorInvalidValue;   // bf16 results only
+    if (a.out2 && (epi != EPI_BIAS || a.out_panels || a.n_split % 8 != 0 || a.n_split <= 0 || a.n_split >= a.N)) return hipErrorInvalidValue;
     // streaming stores for bf16 results no cache level could hand on whole (threshold: twice the 32 MB of L2)
     const bool nt = big && (size_t)a.M * a.N * 2 >= ((size_t)64 << 20);
     switch (epi) {

@@ -208,7 +208,9 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] += b[e];
     if constexpr (EPI == EPI_BIAS) {
-      *(bf16x4 *)((__bf16 *)p.out + (size_t)m * p.ldo + nn) = to_bf16x4(v);
+      __bf16 *dst = (p.out2 && nn >= p.n_split) ? (__bf16 *)p.out2 + (size_t)m * p.ldo2 + (nn - p.n_split)
+                                                 : (__bf16 *)p.out + (size_t)m * p.ldo + nn;
+      *(bf16x4 *)dst = to_bf16x4(v);
     } else if constexpr (EPI == EPI_BIAS_GELU) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
@@ -255,6 +257,7 @@ bool gemm_small_applies(int32_t M) { return M <= 1024; }
 hipError_t launch_gemm_small(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   if (a.N % SBN != 0 || a.K % SBK != 0 || a.K <= 0 || a.a_panels || a.out_panels) return hipErrorInvalidValue;
+  if (a.out2 && (epi != EPI_BIAS || a.n_split % 4 != 0 || a.n_split <= 0 || a.n_split >= a.N)) return hipErrorInvalidValue;
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
     switch (epi) {

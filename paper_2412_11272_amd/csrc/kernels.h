@@ -53,6 +53,11 @@ struct GemmArgs {
   // A_LN only
   const float *ln_g, *ln_b; // [K]
   float ln_eps;
+  // bf16 results only (EPI_BIAS on the MFMA path): columns [n_split, N) of the result go to out2 (row stride ldo2) instead
+  // of out, starting at its column 0 -- one product feeding two buffers (queries | keys and values).  n_split % 8 == 0.
+  void *out2;
+  int32_t n_split, ldo2;
+  int32_t prefer_large;     // stay on the large-batch kernels whatever M is (a product that streams a huge weight matrix)
   int32_t prefer_small;     // run on the small-batch kernel even if M is above its usual limit (the first convolution
                             // of a small batch has twice as many rows as the batch has tokens)
 };
