@@ -7,7 +7,7 @@
 // Differences from the large-batch kernels of gemm_bf16.hip:
 //   * 32-row output tiles, 32, 64 or 128 columns wide (NB column blocks of 32), so that even a 75-token batch spreads
 //     over dozens of compute units (75 x 384: 36 workgroups instead of 3); the launcher takes the widest tile that
-//     still leaves about 128 workgroups, because every column tile re-reads (and with A_LN re-normalises) the same
+//     still leaves about 160 workgroups, because every column tile re-reads (and with A_LN re-normalises) the same
 //     32 activation rows;
 //   * the four waves of a workgroup split the reduction: in every 64-deep K step wave w multiplies the k slice
 //     [16 w, 16 w + 16) with one 32x32x16 MFMA, and the four partial tiles are added in a fixed order through LDS
@@ -232,11 +232,12 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
   }
 }
 
-// Widest tile (in 32-column blocks) that divides N and still leaves about 128 workgroups; 1 if even that gives fewer.
+// Widest tile (in 32-column blocks) that divides N and still leaves at least 160 workgroups; 1 if even that gives fewer.
 int pick_blocks(const GemmArgs &a) {
+  constexpr int min_wgs = 160;     // measured: 425 tokens prefer 168-224 wide tiles to 336-448 narrower ones, 125 tokens 192-256 to 96-128
   const long rows = (a.M + SBM - 1) / SBM;
   for (int nb = 4; nb > 1; nb >>= 1)
-    if (a.N % (nb * SBN) == 0 && rows * (a.N / (nb * SBN)) >= 128) return nb;
+    if (a.N % (nb * SBN) == 0 && rows * (a.N / (nb * SBN)) >= min_wgs) return nb;
   return 1;
 }
 
