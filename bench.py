@@ -287,6 +287,7 @@ def main():
     ap.add_argument("--lanes", type=int, default=0,
                     help="lanes of the encoder in the timed region (0 = the library's default); per-kernel durations are "
                          "always measured with one lane, i.e. with kernels running one at a time")
+    ap.add_argument("--graphs", action="store_true", help="replay one-lane batches from captured HIP graphs (wf_encoder_set_graphs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--encoder-only", action="store_true",
                     help="time the encoder hot path only; by default the legs of the other rows (front end, decoder-side "
@@ -334,6 +335,8 @@ def main():
     enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)
     if args.lanes > 0:
         enc.set_lanes(args.lanes)
+    if args.graphs:
+        enc.set_graphs(True)
     lanes_timed = enc.get_lanes()
     flat, offs, nf = wf.pack_mels(mels)
     mel = torch.from_numpy(flat).cuda()
