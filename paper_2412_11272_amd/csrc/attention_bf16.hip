@@ -11,6 +11,9 @@
 // accumulators, so the row max, the rescale factor and the row sum are per-lane scalars, and the
 // S^T accumulator registers are, as they stand, the second operand of the P.V MFMA: lane group
 // g = lane/32 holds keys {8a + 4g + b}, and the V^T fragment is read with the same key order.
+#include <algorithm>
+#include <mutex>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -245,6 +248,207 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Variant for batches too small to fill the chip with 128-query work items (one stream's buffer: a few hundred
+// tokens).  There the kernel's duration is the length of one workgroup's chain of key tiles, so the chain is cut
+// four ways: a workgroup takes 32 queries of one (stream, head) and its four waves walk the key tiles w, w + 4,
+// w + 8, ... each with its own running maximum, sum and output accumulators, reading tiles it loads itself into
+// LDS buffers of its own (no workgroup barrier inside the loop).  At the end the four partial results are rescaled
+// to the common maximum and added in wave order through LDS (deterministic).  Same arithmetic per tile as
+// attention_bf16_kernel; the grouping of the tiles differs, so results agree to fp32 rounding of the sums, not bit
+// for bit.
+__global__ void __launch_bounds__(256) attention_bf16_keysplit_kernel(AttnArgs p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_ks[];   // per wave: K[2][8 KB] then V[2][8 KB]
+
+  const int heads8 = (p.n_heads + 7) & ~7;
+  const int unit = blockIdx.x / heads8;               // (work item, quarter of its 128 queries)
+  const int item = unit >> 2, sub = unit & 3;
+  const int w1 = p.work[2 * item + 1];
+  const int rot = (((w1 >> 20) & 7) * (p.n_heads & 7)) & 7;
+  const int head = (blockIdx.x % heads8 + heads8 - rot) % heads8;
+  if (head >= p.n_heads) return;
+  const int stream = p.work[2 * item];
+  const int q0 = (w1 & 0xFFFFF) + 32 * sub;
+  const int tok0 = p.cu_q[stream];
+  const int Lq = p.cu_q[stream + 1] - tok0;
+  if (q0 >= Lq) return;
+  const int ktok0 = p.cu_kv[stream];
+  const int L = p.cu_kv[stream + 1] - ktok0;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lg = lane >> 5;
+  const int ldq = p.ldq, ld = p.ldkv;
+  const __bf16 *Qb = (const __bf16 *)p.q + (size_t)tok0 * ldq + head * 64;
+  const __bf16 *Kb = (const __bf16 *)p.k + (size_t)ktok0 * ld + head * 64;
+  const __bf16 *Vb = (const __bf16 *)p.v + (size_t)ktok0 * ld + head * 64;
+  unsigned char *myK = smem_ks + wave * 32768, *myV = myK + 16384;
+
+  int qrow = q0 + l32;
+  const bool q_valid = qrow < Lq;
+  qrow = q_valid ? qrow : Lq - 1;
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8 *)(Qb + (size_t)qrow * ldq + ks * 16 + lg * 8);
+
+  f32x16 o[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[t][r] = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;
+  const float c = p.scale * 1.4426950408889634f;
+
+  // one wave loads a whole tile: 8 instructions of 8 rows for K, 8 for V
+  const int lrow = lane >> 3;
+  auto issue = [&](int kt, int buf) {
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      const int rt = g * 8 + lrow;
+      int key = kt * BKV + rt;
+      key = key < L ? key : L - 1;
+      const __bf16 *srck = Kb + (size_t)key * ld + ((lane & 7) ^ ((rt >> 1) & 7)) * 8;
+      const __bf16 *srcv = Vb + (size_t)key * ld + ((lane & 7) ^ v_swizzle(rt)) * 8;
+      __builtin_amdgcn_global_load_lds((const glb_void *)srck, (lds_void *)(myK + buf * 8192 + g * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const glb_void *)srcv, (lds_void *)(myV + buf * 8192 + g * 1024), 16, 0, 0);
+    }
+  };
+  const int r16 = lane & 15;
+  const int tr_key = r16 >> 2;
+  const int tr_feat = ((lane >> 4) & 1) * 16 + (r16 & 3) * 4;
+
+  const int n_tiles = (L + BKV - 1) / BKV;
+  int buf = 0;
+  if (wave < n_tiles) issue(wave, 0);
+  for (int kt = wave; kt < n_tiles; kt += 4, buf ^= 1) {
+    const int key0 = kt * BKV;
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): this wave's tile kt has landed (nobody else touches these buffers)
+    if (kt + 4 < n_tiles) issue(kt + 4, buf ^ 1);
+    const unsigned char *cK = myK + buf * 8192, *cV = myV + buf * 8192;
+    f32x16 s[2];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb2][r] = 0.0f;
+      const int row = kb2 * 32 + l32;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 kf = *(const bf16x8 *)(cK + row * 128 + (((2 * ks + lg) ^ ((row >> 1) & 7)) << 4));
+        s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb2], 0, 0, 0);
+      }
+    }
+    if (key0 + BKV > L) {
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kb2 * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+          if (key >= L) s[kb2][r] = -INFINITY;
+        }
+    }
+    float tmax = s[0][0];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb2][r]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax);       // finite: every tile has at least one valid key
+    if (__any(m_new > m_run)) {
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_run * c;
+    float psum = 0.0f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        f32x4 e0, e1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          e0[e] = __builtin_amdgcn_exp2f(s[kb2][8 * h + e] * c - mc);
+          e1[e] = __builtin_amdgcn_exp2f(s[kb2][8 * h + 4 + e] * c - mc);
+          psum += e0[e] + e1[e];
+        }
+        const bf16x4 b0 = to_bf16x4(e0), b1 = to_bf16x4(e1);
+        pf[kb2][h] = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    l_run += psum;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int fchunk = (t * 32 + tr_feat) >> 3;
+      const int fin = ((t * 32 + tr_feat) & 7) * 2;
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int k0 = kb2 * 32 + 16 * h + 4 * lg + tr_key;
+          const int k1 = k0 + 8;
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cV + k0 * 128 + ((fchunk ^ v_swizzle(k0)) << 4) + fin));
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cV + k1 * 128 + ((fchunk ^ v_swizzle(k1)) << 4) + fin));
+          const bf16x4 w0 = __builtin_bit_cast(bf16x4, v0), w1b = __builtin_bit_cast(bf16x4, v1);
+          const bf16x8 vf = __builtin_shufflevector(w0, w1b, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb2][h], o[t], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- merge the four waves' partial results.  sM / sL: [wave][query]; sO: [wave][query][64 features] fp32, laid
+  // over the tile buffers (every wave is past its last tile read once it reaches the barrier).
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  float *sM = (float *)smem_ks;                   // 4 x 32
+  float *sL = sM + 128;                           // 4 x 32
+  float *sO = sL + 128;                           // 4 x 32 x 64
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (lg == 0) sM[wave * 32 + l32] = m_run;
+  __syncthreads();
+  float M = sM[l32];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) M = fmaxf(M, sM[w * 32 + l32]);
+  const float sc = __builtin_amdgcn_exp2f((m_run - M) * c);    // 0 for a wave that saw no tile (m_run = -inf)
+  if (lg == 0) sL[wave * 32 + l32] = l_tot * sc;
+  // lane holds, of query l32, features t*32 + 8*g + 4*lg + e  (o[t][4*g + e])
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = o[t][g * 4 + e] * sc;
+      *(f32x4 *)(sO + (wave * 32 + l32) * 64 + t * 32 + g * 8 + lg * 4) = v;
+    }
+  __syncthreads();
+  // thread -> query tid / 8, features (tid % 8) * 8 .. + 7
+  const int qq = tid >> 3, f0 = (tid & 7) * 8;
+  if (q0 + qq < Lq) {
+    float lsum = sL[qq];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) lsum += sL[w * 32 + qq];
+    const float inv = 1.0f / lsum;
+    f32x4 a0 = *(const f32x4 *)(sO + qq * 64 + f0), a1 = *(const f32x4 *)(sO + qq * 64 + f0 + 4);
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const f32x4 b0 = *(const f32x4 *)(sO + (w * 32 + qq) * 64 + f0), b1 = *(const f32x4 *)(sO + (w * 32 + qq) * 64 + f0 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a0[e] += b0[e]; a1[e] += b1[e]; }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { a0[e] *= inv; a1[e] *= inv; }
+    const bf16x4 c0 = to_bf16x4(a0), c1 = to_bf16x4(a1);
+    __bf16 *orow = (__bf16 *)p.out + (size_t)(tok0 + q0 + qq) * p.d_model + head * 64 + f0;
+    *(bf16x8 *)orow = __builtin_shufflevector(c0, c1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+}
+
 }  // namespace
 
 int attention_q_tile() { return BQ; }
@@ -257,6 +461,17 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   if (a.causal) {
     if (a.cu_q != a.cu_kv) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attention_bf16_kernel<true>, grid, dim3(256), 0, s, a);
+  } else if (std::min<long>(4L * a.n_work, a.M / 32 + a.B) * a.n_heads <= 256) {
+    // so few queries that even 32-query workgroups (one per compute unit: they take 128 KB of LDS) fit the chip in one go:
+    // cut the key loop four ways instead.  (8 streams of 325 tokens x 16 heads = 1408 such workgroups ran 12 % slower.)
+    constexpr int smem = 4 * 32768;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+      attr_err = hipFuncSetAttribute((const void *)attention_bf16_keysplit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    hipLaunchKernelGGL(attention_bf16_keysplit_kernel, dim3(4 * grid.x), dim3(256), smem, s, a);
   } else {
     hipLaunchKernelGGL(attention_bf16_kernel<false>, grid, dim3(256), 0, s, a);
   }

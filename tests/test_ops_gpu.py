@@ -94,14 +94,16 @@ def test_layernorm(M, d):
 
 
 LENS = [[1], [75], [64, 65, 63], [128, 129, 1, 2, 300], [1525, 75, 700]]
+# (lens, heads): few queries -> the kernel that splits the key loop over the waves (one stream's buffer: at most 256
+# workgroups of 32 queries); [1525, 75, 700] x 3 heads and the last case are beyond that and run with 128-query work items
+CASES = [(l, 3) for l in LENS] + [([1525, 700, 300, 129, 128, 75, 64, 1], 20)]
 
 
-@pytest.mark.parametrize("lens", LENS)
+@pytest.mark.parametrize("lens,n_heads", CASES)
 @pytest.mark.parametrize("sharp", [1.0, 6.0])
 @pytest.mark.parametrize("precision", [wf.WF_PRECISION_BF16, wf.WF_PRECISION_F32])
-def test_attention(lens, sharp, precision):
+def test_attention(lens, n_heads, sharp, precision):
     import torch
-    n_heads = 3
     d = 64 * n_heads
     M = sum(lens)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
