@@ -327,9 +327,10 @@ def main():
     prop = torch.cuda.get_device_properties(0)
     # dense bf16 MFMA peak = CUs x 4096 flop per clock x clock; the published 2.5 PFLOP/s is 256 CUs at 2.4 GHz and is
     # what every fraction here is quoted against, whatever the device reports
+    khz = wf.device_info()["clock_khz"]
     peak_note = {"used_tflops": PEAK_BF16_TFLOPS, "device": prop.name, "compute_units": int(prop.multi_processor_count),
-                 "max_clock_ghz": round(getattr(prop, "clock_rate", 0) / 1e6, 3),
-                 "from_device_tflops": round(prop.multi_processor_count * 4096 * getattr(prop, "clock_rate", 0) * 1e3 / 1e12, 1)}
+                 "max_clock_ghz": round(khz / 1e6, 3),
+                 "from_device_tflops": round(prop.multi_processor_count * 4096 * khz * 1e3 / 1e12, 1)}
     wl = synth.workload(args.workload)
     weights, hush, mels = synth.materialize(wl)
     enc = wf.encoder_for_workload(wl, weights, hush, wf.WF_PRECISION_BF16)

@@ -184,6 +184,10 @@ int wf_encoder_graph_stats(const wf_encoder *enc, int64_t *replays, int64_t *cap
 /* The configuration the encoder was created with (ln_eps as resolved). */
 int wf_encoder_get_config(const wf_encoder *enc, wf_config *cfg);
 
+/* Compute units and peak shader clock (kHz) of the current HIP device, as the runtime reports them (either pointer
+ * may be NULL).  WF_E_HIP without a device.  For reports: the dense bf16 MFMA peak is units x 4096 flop x clock. */
+int wf_device_info(int32_t *compute_units, int32_t *clock_khz);
+
 /*
  * Diagnostic, host only (no GPU call): the work units the MFMA GEMM launches for an M x N result with tile_m x tile_n
  * tiles, in workgroup order, as (first row, first column, width in columns) triples in units[3 * i .. 3 * i + 2]

@@ -101,7 +101,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
-           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map"]
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_device_info"]
 
 
 def lib() -> C.CDLL:
@@ -148,6 +148,7 @@ def lib() -> C.CDLL:
     L.wf_encoder_get_config.argtypes = [C.c_void_p, C.POINTER(WfConfig)]
     L.wf_encoder_set_lanes.argtypes = [C.c_void_p, C.c_int32]
     L.wf_encoder_get_lanes.argtypes = [C.c_void_p]
+    L.wf_device_info.argtypes = [_ip, _ip]
     L.wf_gemm_tile_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _ip, C.c_int32]
     L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
@@ -581,3 +582,10 @@ def gemm_tile_map(M: int, N: int, tile_m: int = 256, tile_n: int = 256) -> np.nd
     n = lib().wf_gemm_tile_map(M, N, tile_m, tile_n, units.ctypes.data_as(_ip), cap)
     _check(min(n, 0))
     return units[:n]
+
+
+def device_info() -> dict:
+    """Compute units and maximum shader clock (kHz) of the current device, as the HIP runtime reports them."""
+    cu, khz = C.c_int32(0), C.c_int32(0)
+    _check(lib().wf_device_info(C.byref(cu), C.byref(khz)))
+    return {"compute_units": cu.value, "clock_khz": khz.value}

@@ -639,6 +639,20 @@ int wf_encoder_kernel_stats(wf_encoder *e, wf_kernel_stat *stats, int32_t n_stat
   return collect_stats(e, stats, n_stats);
 }
 
+int wf_device_info(int32_t *compute_units, int32_t *clock_khz) {
+  int dev = 0, v = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (compute_units) {
+    HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    *compute_units = v;
+  }
+  if (clock_khz) {
+    HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, dev));
+    *clock_khz = v;
+  }
+  return WF_OK;
+}
+
 int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32_t *units, int32_t capacity) {
   if (!units || capacity < 0) return fail(WF_E_INVALID_ARG, "units is NULL or capacity negative");
   if (M < 1 || N < 1 || tile_m < 1 || tile_n < 2 || tile_n % 2 || N % tile_n) return fail(WF_E_INVALID_ARG, "need M, N >= 1 and N a multiple of an even tile_n");
