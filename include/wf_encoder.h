@@ -209,6 +209,9 @@ int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32
  *                   (the projections of a transformer block: QKV, fc1, and out-projection / fc2)
  * wf_op_layernorm   out[r, :] = (x[r, :] - mean) / sqrt(biased var + eps) * g + b, x fp32 [M, d],
  *                   out dtype WF_DTYPE_*; d % 4 == 0, d <= 2048.
+ * wf_op_ln_linear   bf16 path, small batches only (M <= 1024, else WF_E_CAPACITY): out = epilogue(LayerNorm(x) . w^T + bias)
+ *                   with x fp32 [M, K] normalised on the way into the product (K <= 2048), w bf16 [N, K] row-major,
+ *                   out bf16 [M, N]; epilogue 0 or 1 as above.  What QKV and fc1 run as for a single stream's buffer.
  * wf_op_attention   bidirectional softmax attention restricted to each stream, head size 64:
  *                   qkv [M, 3 * 64 * n_heads] (q | k | v), out [M, 64 * n_heads], cu_seqlens_host
  *                   [B+1] with cu_seqlens_host[0] == 0 and no empty stream.  Allocates a small
@@ -218,6 +221,8 @@ int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const 
                  int32_t M, int32_t N, int32_t K, int32_t epilogue, void *hip_stream);
 int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, void *out_dev, int32_t out_dtype,
                     int32_t M, int32_t d, float eps, void *hip_stream);
+int wf_op_ln_linear(const float *x_dev, const float *g_dev, const float *b_dev, float eps, const void *w_dev,
+                    const float *bias_dev, void *out_dev, int32_t M, int32_t N, int32_t K, int32_t epilogue, void *hip_stream);
 int wf_op_attention(int32_t precision, const void *qkv_dev, void *out_dev, const int32_t *cu_seqlens_host, int32_t B,
                     int32_t n_heads, void *hip_stream);
 /*

@@ -101,7 +101,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
-           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_device_info"]
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_device_info", "wf_op_ln_linear"]
 
 
 def lib() -> C.CDLL:
@@ -149,6 +149,8 @@ def lib() -> C.CDLL:
     L.wf_encoder_set_lanes.argtypes = [C.c_void_p, C.c_int32]
     L.wf_encoder_get_lanes.argtypes = [C.c_void_p]
     L.wf_device_info.argtypes = [_ip, _ip]
+    L.wf_op_ln_linear.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     L.wf_gemm_tile_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _ip, C.c_int32]
     L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
@@ -589,3 +591,15 @@ def device_info() -> dict:
     cu, khz = C.c_int32(0), C.c_int32(0)
     _check(lib().wf_device_info(C.byref(cu), C.byref(khz)))
     return {"compute_units": cu.value, "clock_khz": khz.value}
+
+
+def op_ln_linear(x, g, b, w, bias, out, epilogue: int, eps: float = 1e-5, stream=None):
+    """out = epilogue(LayerNorm(x) w^T + bias) on the small-batch kernel (x fp32 [M, K], w bf16 [N, K], out bf16 [M, N])."""
+    import torch
+    M, K = x.shape
+    N = w.shape[0]
+    s = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().wf_op_ln_linear(C.c_void_p(x.data_ptr()), C.c_void_p(g.data_ptr()), C.c_void_p(b.data_ptr()), eps,
+                                 C.c_void_p(w.data_ptr()), C.c_void_p(bias.data_ptr()), C.c_void_p(out.data_ptr()), M, N, K, epilogue,
+                                 C.c_void_p(s)))
+    return out

@@ -676,6 +676,22 @@ int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const 
   return WF_OK;
 }
 
+int wf_op_ln_linear(const float *x_dev, const float *g_dev, const float *b_dev, float eps, const void *w_dev, const float *bias_dev,
+                    void *out_dev, int32_t M, int32_t N, int32_t K, int32_t epilogue, void *hip_stream) {
+  if (!x_dev || !g_dev || !b_dev || !w_dev || !bias_dev || !out_dev) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (M < 1 || N < 128 || N % 128 || K < 64 || K % 64 || K > 2048) return fail(WF_E_INVALID_ARG, "need M >= 1, N %% 128 == 0, K %% 64 == 0, K <= 2048");
+  if (!gemm_small_applies(M)) return fail(WF_E_CAPACITY, "M = %d: the fused LayerNorm operand exists for small batches only", M);
+  if (epilogue < 0 || epilogue > 1) return fail(WF_E_INVALID_ARG, "epilogue = %d (0: bias, 1: bias + GELU)", epilogue);
+  if (!(eps > 0.0f)) return fail(WF_E_INVALID_ARG, "eps must be positive");
+  GemmArgs a{};
+  a.A = x_dev; a.W = w_dev; a.bias = bias_dev; a.out = out_dev;
+  a.M = M; a.N = N; a.K = K; a.lda = K; a.ldo = N;
+  a.ln_g = g_dev; a.ln_b = b_dev; a.ln_eps = eps;
+  hipError_t err = launch_gemm_bf16(a, A_LN, (Epilogue)epilogue, (hipStream_t)hip_stream);
+  if (err != hipSuccess) return fail(WF_E_HIP, "ln_linear launch: %s", hipGetErrorString(err));
+  return WF_OK;
+}
+
 int wf_op_layernorm(const float *x_dev, const float *g_dev, const float *b_dev, void *out_dev, int32_t out_dtype, int32_t M,
                     int32_t d, float eps, void *hip_stream) {
   if (!x_dev || !g_dev || !b_dev || !out_dev) return fail(WF_E_INVALID_ARG, "NULL pointer");

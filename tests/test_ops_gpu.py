@@ -93,6 +93,41 @@ def test_layernorm(M, d):
     assert _rel(outb.float().cpu().numpy(), ref) < 5e-3
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (75, 1152, 384), (425, 2048, 512), (33, 256, 2048), (1024, 384, 1280)])
+@pytest.mark.parametrize("epi", [0, 1])
+def test_layernorm_fused_into_the_small_batch_product(M, N, K, epi):
+    """QKV / fc1 of a single stream's buffer: the product normalises its fp32 operand itself.  Against LayerNorm
+    followed by the product in the oracle, with the normalised rows rounded to bf16 as the kernel stores them; rows
+    with a mean far from zero, an outlier in first place (the kernel shifts its sums by that element) and a
+    constant row are in the batch."""
+    import torch
+    rng = np.random.default_rng(M + N + K + epi)
+    x = (rng.standard_normal((M, K)) * 1.5 + 0.3).astype(np.float32)
+    x[0] = 7.25                                              # constant row -> exactly the shift
+    if M > 4:
+        x[1] += 300.0                                        # mean 200 standard deviations away from zero
+        x[2, 0] = 500.0                                      # the pivot of the shifted sums is an outlier
+        x[3] *= 1e-3
+    g = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    w = _bf16_round(rng.standard_normal((N, K)) * 0.05)
+    bias = rng.standard_normal(N).astype(np.float32)
+    u = O.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    u16 = _bf16_round(u).float().numpy().astype(np.float64)                  # what reaches the matrix pipe
+    ref = O.linear(u16, w.float().numpy().astype(np.float64), bias.astype(np.float64))
+    if epi == 1:
+        ref = O.gelu(ref)
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    wf.op_ln_linear(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda(), w.cuda(),
+                    torch.from_numpy(bias).cuda(), out, epi)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    # bf16 rounding of u flips where the kernel's fp32 statistics differ from the oracle's in the last bit: a few
+    # elements of u move by one bf16 step (2^-8 relative), which the 5e-3 on the result covers
+    assert _rel(got, ref) < 6e-3
+
+
 LENS = [[1], [75], [64, 65, 63], [128, 129, 1, 2, 300], [1525, 75, 700]]
 # (lens, heads): few queries -> the kernel that splits the key loop over the waves (one stream's buffer: at most 256
 # workgroups of 32 queries); [1525, 75, 700] x 3 heads and the last case are beyond that and run with 128-query work items
