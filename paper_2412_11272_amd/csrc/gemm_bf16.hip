@@ -1,5 +1,7 @@
 // bf16 MFMA GEMMs for gfx950:  out = epilogue(A . W^T),  A [M, K] activations, W [N, K] weights, fp32
-// accumulation.  Two kernels share the tiling:
+// accumulation.  launch_gemm_bf16 sends batches of up to about a thousand rows to the small-batch kernel of
+// gemm_small.hip (latency-bound regime, LayerNorm fused into the operand); everything else runs here.  Two kernels
+// share the tiling:
 //
 //   gemm_bf16_dl_kernel   (v_mfma_f32_16x16x32_bf16) the projections of a transformer block (QKV, out, fc1,
 //                         fc2) and, when a tap is a whole number of K steps, the two convolutions of the
