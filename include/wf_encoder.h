@@ -199,6 +199,13 @@ int wf_device_info(int32_t *compute_units, int32_t *clock_khz);
 int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32_t *units, int32_t capacity);
 
 /*
+ * Diagnostic, host only: the tile (rows x columns of the result per workgroup) the bf16 MFMA GEMM picks for a plain
+ * M x N product: 320 x 256 or 256 x 256 for large batches (whichever finishes its last round of the chip earlier),
+ * 128 x 128 below that, 0 x 0 when M is small enough for the small-batch kernel.  N must be a multiple of 128.
+ */
+int wf_gemm_tile_choice(int32_t M, int32_t N, int32_t *tile_m, int32_t *tile_n);
+
+/*
  * Operator-level entry points: single steps of the encoder on caller-provided DEVICE buffers, for
  * per-operator checks and micro-benchmarks.  precision selects the kernel family and the element
  * type of activations and weights (WF_PRECISION_BF16: bf16, WF_PRECISION_F32: fp32).

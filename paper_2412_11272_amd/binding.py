@@ -101,7 +101,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
-           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_device_info", "wf_op_ln_linear"]
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_gemm_tile_choice", "wf_device_info", "wf_op_ln_linear"]
 
 
 def lib() -> C.CDLL:
@@ -152,6 +152,7 @@ def lib() -> C.CDLL:
     L.wf_op_ln_linear.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     L.wf_gemm_tile_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _ip, C.c_int32]
+    L.wf_gemm_tile_choice.argtypes = [C.c_int32, C.c_int32, _ip, _ip]
     L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
     L.wf_encoder_graph_stats.argtypes = [C.c_void_p, _lp, _lp, _lp]
@@ -584,6 +585,13 @@ def gemm_tile_map(M: int, N: int, tile_m: int = 256, tile_n: int = 256) -> np.nd
     n = lib().wf_gemm_tile_map(M, N, tile_m, tile_n, units.ctypes.data_as(_ip), cap)
     _check(min(n, 0))
     return units[:n]
+
+
+def gemm_tile_choice(M: int, N: int) -> tuple:
+    """(tile rows, tile columns) the bf16 MFMA GEMM picks for an M x N product; (0, 0) = small-batch kernel (host only)."""
+    tm, tn = C.c_int32(0), C.c_int32(0)
+    _check(lib().wf_gemm_tile_choice(M, N, C.byref(tm), C.byref(tn)))
+    return tm.value, tn.value
 
 
 def device_info() -> dict:

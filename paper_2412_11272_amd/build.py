@@ -17,7 +17,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", 
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA results land in architectural VGPRs: the softmax and the epilogues consume them with VALU
          # instructions, and the AGPR form costs a v_accvgpr_read per value
-         "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         # extra compiler flags for experiments (e.g. -D switches of compile-time variants)
+         *os.environ.get("WF_HIPCC_EXTRA", "").split()]
 
 
 def _compile(src: str) -> str:

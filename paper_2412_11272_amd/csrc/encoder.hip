@@ -661,6 +661,13 @@ int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32
   return n;
 }
 
+int wf_gemm_tile_choice(int32_t M, int32_t N, int32_t *tile_m, int32_t *tile_n) {
+  if (!tile_m || !tile_n) return fail(WF_E_INVALID_ARG, "NULL pointer");
+  if (M < 1 || N < 128 || N % 128) return fail(WF_E_INVALID_ARG, "need M >= 1 and N a positive multiple of 128");
+  gemm_tile_choice(M, N, tile_m, tile_n);
+  return WF_OK;
+}
+
 // ---- operator-level entry points -------------------------------------------------------------
 int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const float *bias_dev, void *out_dev, int32_t M,
                  int32_t N, int32_t K, int32_t epilogue, void *hip_stream) {

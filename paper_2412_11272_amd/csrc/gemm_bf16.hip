@@ -264,8 +264,12 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   const int lrow = lane >> 3;
   const __bf16 *A = (const __bf16 *)p.A;
   const __bf16 *W = (const __bf16 *)p.W;
-  const __bf16 *xptr[XL];
-  const __bf16 *wptr[WL];
+  // Plain operands are addressed as a uniform base plus a 32-bit byte offset per lane (half the registers of a
+  // pointer per load instruction; the launcher keeps such operands under 4 GiB); the gathered convolution
+  // operand keeps full pointers, since a masked tap redirects the whole address.
+  constexpr bool OFFS = AMODE != A_CONV3;
+  const __bf16 *xptr[OFFS ? 1 : XL];
+  unsigned xoff[OFFS ? XL : 1], woff[WL];
   [[maybe_unused]] int xflags[XL];      // A_CONV3: bit 0 = first tap lies before the stream, bit 1 = last tap lies after it
 #pragma unroll
   for (int i = 0; i < XL; ++i) {
@@ -278,8 +282,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
       xptr[i] = A + (long)p.row_src[row] * p.C + lch * 8;
       xflags[i] = p.row_flags[row];
     } else {
-      xptr[i] = p.a_panels ? A + ((size_t)(row >> 8) * (p.K >> 6) << 14) + ((row & 255) << 6) + lch * 8   // panel layout
-                           : A + (size_t)row * p.lda + lch * 8;
+      xoff[i] = 2u * (p.a_panels ? (((unsigned)(row >> 8) * (unsigned)(p.K >> 6)) << 14) + ((row & 255) << 6) + lch * 8   // panel layout
+                                 : (unsigned)row * (unsigned)p.lda + lch * 8);
     }
   }
 #pragma unroll
@@ -287,8 +291,8 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     const int rt = (i * NW + wave) * 8 + lrow;
     const int lch = (lane & 7) ^ ((rt >> 1) & 7);
     const int n = n0 + rt;
-    wptr[i] = p.w_panels ? W + ((size_t)(n >> 8) * (p.K >> 6) << 14) + ((n & 255) << 6) + lch * 8
-                         : W + (size_t)n * p.K + lch * 8;
+    woff[i] = 2u * (p.w_panels ? (((unsigned)(n >> 8) * (unsigned)(p.K >> 6)) << 14) + ((n & 255) << 6) + lch * 8
+                               : (unsigned)n * (unsigned)p.K + lch * 8);
   }
 
   [[maybe_unused]] const int kpt = AMODE == A_CONV3 ? p.C / BK : 0;     // K steps per tap
@@ -297,19 +301,24 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     const int ka = p.a_panels ? kt << 14 : k0;     // panel layout: the next 64-column chunk is 256 * 64 elements on
     // A_CONV3: K steps [0, kpt) are tap 0, [2 kpt, 3 kpt) tap 2; the flag bit that zeroes this step's tap
     const int dead = AMODE == A_CONV3 ? (kt < kpt ? 1 : (kt >= 2 * kpt ? 2 : 0)) : 0;
+    // the K offset goes into the 32-bit lane offset, so that the address stays "uniform base + zero-extended
+    // 32-bit offset" inside the loop and the load takes the scalar-base form (one address register per load)
+    const unsigned kb = 2u * (unsigned)ka;
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
-      const __bf16 *src = xptr[i] + ka;
-      if constexpr (AMODE == A_CONV3) src = (xflags[i] & dead) ? (const __bf16 *)g_zero16 : src;
+      const void *src;
+      if constexpr (AMODE == A_CONV3) src = (xflags[i] & dead) ? (const void *)g_zero16 : (const void *)(xptr[i] + ka);
+      else src = (const unsigned char *)A + (unsigned)(xoff[i] + kb);
       __builtin_amdgcn_global_load_lds((const glb_void *)src,
                                        (lds_void *)(sX + slot * BM * 128 + (i * NW + wave) * 1024), 16, 0, 0);
     }
   };
   auto issue_w = [&](int kt, int slot) {
     const int kw = p.w_panels ? kt << 14 : kt * BK;
+    const unsigned kb = 2u * (unsigned)kw;
 #pragma unroll
     for (int i = 0; i < WL; ++i)
-      __builtin_amdgcn_global_load_lds((const glb_void *)(wptr[i] + kw),
+      __builtin_amdgcn_global_load_lds((const glb_void *)((const unsigned char *)W + (unsigned)(woff[i] + kb)),
                                        (lds_void *)(sW + slot * BN * 128 + (i * NW + wave) * 1024), 16, 0, 0);
   };
 
@@ -617,9 +626,16 @@ __host__ __device__ inline bool dl_unit(const GemmArgs &p, int bid, int tiles_m,
   return true;
 }
 
+// LDS bytes of a direct-load kernel: its operand stages, or the epilogue's per-wave transposition slices if those are larger.
+constexpr int dl_smem_bytes(int bm, int bn, int nw, int tm, int deep) {
+  const int stages = (2 * (bm + bn) + (deep == 1 ? bm : (deep == 2 ? bn : 0))) * 128;
+  const int slices = nw * tm * 256;
+  return stages > slices ? stages : slices;
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, bool NT, int AMODE, int DEEP>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) {
-  constexpr int SMEM = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
+  constexpr int SMEM = dl_smem_bytes(BM, BN, WM * WN, BM / WM, DEEP);
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   DlUnit u;
   if (!dl_unit(p, blockIdx.x, (p.M + BM - 1) / BM, p.N / BN, u)) return;
@@ -629,7 +645,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_dl_kernel(GemmArgs p) 
 
 template <int BM, int BN, int WM, int WN, int EPI, bool NT = false, int AMODE = A_PLAIN, int DEEP = 0>
 hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
-  constexpr int smem = (2 * (BM + BN) + (DEEP == 1 ? BM : (DEEP == 2 ? BN : 0))) * 128;
+  constexpr int smem = dl_smem_bytes(BM, BN, WM * WN, BM / WM, DEEP);
   auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, EPI, NT, AMODE, DEEP>;
   static std::once_flag once;
   static hipError_t attr_err = hipSuccess;
@@ -646,6 +662,20 @@ bool use_large_tile(const GemmArgs &a) {
   return (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
 }
 
+// Rows of the large tile: 320 or 256.  The 320-row tile fetches 10 % fewer operand lines per flop (the bound of
+// these kernels) and measures about 7 % faster per flop, but a product is as slow as its last round of the chip,
+// so the choice goes by the estimated makespan: rounds of 256 tiles (a last round cut into half units counts
+// 0.5) times the measured per-tile time ratio of 1.18.
+int large_tile_rows(int M, int N) {
+  auto rounds = [](long tiles) {
+    const long rest = tiles % 256;
+    return (double)(tiles / 256) + (rest == 0 ? 0.0 : (2 * rest <= 256 ? 0.5 : 1.0));
+  };
+  const double t256 = rounds((long)((M + 255) / 256) * (N / 256));
+  const double t320 = 1.18 * rounds((long)((M + 319) / 320) * (N / 256));
+  return t320 < t256 ? 320 : 256;
+}
+
 }  // namespace
 
 hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s) {
@@ -653,6 +683,10 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
   if ((gemm_small_applies(a.M) || a.prefer_small) && !a.prefer_large && !a.a_panels && !a.out_panels) return launch_gemm_small(a, amode, epi, s);
   if (amode == A_LN) return hipErrorInvalidValue;      // the fused LayerNorm operand exists in the small-batch kernel only
   if (a.N % 128 != 0 || a.K % BK != 0 || a.K <= 0) return hipErrorInvalidValue;
+  // operands are addressed with 32-bit byte offsets from their base
+  const size_t a_rows = a.a_panels ? ((size_t)a.M + 255) / 256 * 256 : (size_t)a.M;
+  const size_t a_bytes = amode == A_PLAIN ? a_rows * (size_t)(a.a_panels ? a.K : a.lda) * 2 : 0;
+  if (a_bytes >= ((size_t)1 << 32) || (size_t)a.N * a.K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const bool big = use_large_tile(a);
   if (amode == A_PLAIN) {
     if (a.lda % 8 != 0) return hipErrorInvalidValue;
@@ -660,6 +694,14 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
     if (a.out2 && (epi != EPI_BIAS || a.out_panels || a.n_split % 8 != 0 || a.n_split <= 0 || a.n_split >= a.N)) return hipErrorInvalidValue;
     // streaming stores for bf16 results no cache level could hand on whole (threshold: twice the 32 MB of L2)
     const bool nt = big && (size_t)a.M * a.N * 2 >= ((size_t)64 << 20);
+    if (big && large_tile_rows(a.M, a.N) == 320) {
+      switch (epi) {
+        case EPI_BIAS: return nt ? launch_dl<320, 256, 4, 2, EPI_BIAS, true>(a, s) : launch_dl<320, 256, 4, 2, EPI_BIAS>(a, s);
+        case EPI_BIAS_GELU: return nt ? launch_dl<320, 256, 4, 2, EPI_BIAS_GELU, true>(a, s) : launch_dl<320, 256, 4, 2, EPI_BIAS_GELU>(a, s);
+        case EPI_BIAS_RESID: return launch_dl<320, 256, 4, 2, EPI_BIAS_RESID>(a, s);
+        default: break;     // fp32 store: the 256-row tile below
+      }
+    }
     switch (epi) {
       case EPI_BIAS:
         if (nt) return launch_dl<256, 256, 4, 2, EPI_BIAS, true>(a, s);
@@ -689,6 +731,15 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
                  : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+// Diagnostic: tile rows x columns launch_gemm_bf16 picks for a plain M x N product (0 x 0: the small-batch kernel).
+void gemm_tile_choice(int32_t M, int32_t N, int32_t *bm, int32_t *bn) {
+  GemmArgs a{};
+  a.M = M; a.N = N;
+  if (gemm_small_applies(M)) { *bm = 0; *bn = 0; }
+  else if (!use_large_tile(a)) { *bm = 128; *bn = 128; }
+  else { *bm = large_tile_rows(M, N); *bn = 256; }
 }
 
 // Diagnostic: the work units the direct-load GEMM launches for an M x N result with bm x bn tiles, as

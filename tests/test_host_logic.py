@@ -110,7 +110,9 @@ def test_workload_recipes():
 
 @pytest.mark.parametrize("M,N,tm,tn", [(31694, 3840, 256, 256), (31694, 5120, 256, 256), (31694, 1280, 256, 256), (15847, 3840, 256, 256),
                                        (12000, 4096, 256, 256), (6400, 1280, 128, 128), (75, 384, 128, 128), (1, 128, 128, 128),
-                                       (65536, 2560, 256, 256), (257, 256, 256, 256), (63408, 1280, 256, 256)])
+                                       (65536, 2560, 256, 256), (257, 256, 256, 256), (63408, 1280, 256, 256),
+                                       (31694, 3840, 320, 256), (31694, 5120, 320, 256), (31694, 1280, 320, 256), (12000, 5120, 320, 256),
+                                       (321, 256, 320, 256)])
 def test_gemm_work_units_cover_every_tile_exactly_once(M, N, tm, tn):
     """The workgroup -> tile decoding the GEMM kernel runs (XCD striping, column groups, half-width units for the
     last partial round), enumerated on the host: every column block of every tile row exactly once."""
@@ -125,3 +127,18 @@ def test_gemm_work_units_cover_every_tile_exactly_once(M, N, tm, tn):
     assert cover.min() == 1 and cover.max() == 1
     full = int((units[:, 2] == tn).sum())
     assert full % 256 == 0 or len(units) == full                     # halves only after whole rounds of the chip
+
+
+def test_gemm_tile_choice_follows_the_last_round_of_the_chip():
+    """Small batches -> small-batch kernel; in-between -> 128 x 128; large -> 320 or 256 rows, whichever needs fewer
+    (weighted) rounds of 256 workgroups.  The headline configuration's four projections all take 320 rows."""
+    assert wf.gemm_tile_choice(75, 384) == (0, 0) and wf.gemm_tile_choice(1024, 5120) == (0, 0)
+    assert wf.gemm_tile_choice(6400, 1280) == (128, 128) and wf.gemm_tile_choice(2600, 4096) == (128, 128)
+    for n in (3840, 1280, 5120):
+        assert wf.gemm_tile_choice(31694, n) == (320, 256)
+    # 12000 x 1280: 235 tiles of 256 rows fill one round; 190 tiles of 320 rows would also take one, each 1.18 x as long
+    assert wf.gemm_tile_choice(12000, 1280) == (256, 256)
+    assert wf.gemm_tile_choice(12000, 5120) == (320, 256)
+    with pytest.raises(wf.WfError):
+        wf.gemm_tile_choice(100, 100)
+

@@ -20,9 +20,20 @@ def _rel(got, ref):
 
 # M spans: one partial small tile, several small tiles + ragged tail, enough rows for the large tile, and
 # (the last two) the row count of a 64-stream prompt prefill, where the small tile has to fill the chip
-@pytest.mark.parametrize("M,N,K", [(75, 384, 384), (300, 1152, 384), (1000, 128, 1536), (257, 256, 64),
-                                   (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280),
-                                   (6401, 1280, 1280), (6400, 1280, 5120)])
+LINEAR_SHAPES = [(75, 384, 384), (300, 1152, 384), (1000, 128, 1536), (257, 256, 64),
+                 (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280),
+                 (6401, 1280, 1280), (6400, 1280, 5120), (10001, 2560, 640)]
+
+
+def test_linear_shapes_reach_every_tile_family():
+    """Small-batch kernel, 128 x 128, 256 x 256 and 320 x 256 tiles (the last both with streaming stores, result
+    >= 64 MB, and with plain ones) all occur among the shapes of test_linear_bf16."""
+    picks = {(M, N): wf.gemm_tile_choice(M, N) for M, N, _ in LINEAR_SHAPES}
+    assert set(picks.values()) == {(0, 0), (128, 128), (256, 256), (320, 256)}
+    assert picks[(12500, 3840)] == (320, 256) and picks[(10001, 2560)] == (320, 256) and picks[(12301, 5120)] == (256, 256)
+
+
+@pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
 @pytest.mark.parametrize("epi", [0, 1, 2])
 def test_linear_bf16(M, N, K, epi):
     import torch
