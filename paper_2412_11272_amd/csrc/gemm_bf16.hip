@@ -657,9 +657,11 @@ hipError_t launch_dl(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Large tile when it divides N and there is enough work to fill 256 CUs with it.
+// Large tile when it divides N and there is enough work for it: at least 160 tiles of 256 x 256.  That leaves up to
+// 96 CUs idle in the tile's only round, but a CU's tile runs faster the fewer CUs are active, and from there on the
+// large tile wins or ties on every shape of the benchmark configurations (below, the 128 x 128 tile wins).
 bool use_large_tile(const GemmArgs &a) {
-  return (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 192);
+  return (a.N % 256 == 0) && ((long)((a.M + 255) / 256) * (a.N / 256) >= 160);
 }
 
 // Rows of the large tile: 320 or 256.  The 320-row tile fetches 10 % fewer operand lines per flop (the bound of

@@ -103,7 +103,7 @@ hipError_t launch_embed(const void *table, int table_bf16, const float *pos, con
 hipError_t launch_gather_rows(const void *src, const int32_t *row, void *dst, int32_t n, int32_t row_bytes, hipStream_t s);
 int attention_q_tile();     // query rows per attention work item
 int gemm_dl_tile_map(int32_t M, int32_t N, int32_t bm, int32_t bn, int32_t *units, int32_t cap);   // diagnostic, host only
-void gemm_tile_choice(int32_t M, int32_t N, int32_t *bm, int32_t *bn);                          // diagnostic, host only
+void gemm_tile_choice(int32_t M, int32_t N, int32_t *bm, int32_t *bn);                                                  // diagnostic, host only
 
 // fp32 debug path ------------------------------------------------------------------------------
 hipError_t launch_gemm_f32(const GemmArgs &a, AMode amode, Epilogue epi, hipStream_t s);

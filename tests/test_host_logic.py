@@ -133,7 +133,8 @@ def test_gemm_tile_choice_follows_the_last_round_of_the_chip():
     """Small batches -> small-batch kernel; in-between -> 128 x 128; large -> 320 or 256 rows, whichever needs fewer
     (weighted) rounds of 256 workgroups.  The headline configuration's four projections all take 320 rows."""
     assert wf.gemm_tile_choice(75, 384) == (0, 0) and wf.gemm_tile_choice(1024, 5120) == (0, 0)
-    assert wf.gemm_tile_choice(6400, 1280) == (128, 128) and wf.gemm_tile_choice(2600, 4096) == (128, 128)
+    assert wf.gemm_tile_choice(6400, 1280) == (128, 128) and wf.gemm_tile_choice(2600, 3072) == (128, 128)
+    assert wf.gemm_tile_choice(2600, 4096) == (256, 256)          # 176 tiles of 256 x 256: from 160 on the large tile
     for n in (3840, 1280, 5120):
         assert wf.gemm_tile_choice(31694, n) == (320, 256)
     # 12000 x 1280: 235 tiles of 256 rows fill one round; 190 tiles of 320 rows would also take one, each 1.18 x as long
