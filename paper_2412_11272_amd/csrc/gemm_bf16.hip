@@ -240,7 +240,8 @@ typedef __attribute__((address_space(1))) void glb_void;
 __device__ __attribute__((aligned(16))) unsigned int g_zero16[4];
 
 // One BM x BN output tile at (m0, n0), computed by the whole workgroup.  SMEM: bytes of LDS the kernel owns;
-// NT: streaming stores for bf16 results; AMODE: plain or gathered convolution operand; DEEP: which operand
+// NT: streaming stores for bf16 results; AMODE: plain or gathered convolution operand; DEEP: 3 = four LDS stages
+// for both operands, requested three K steps ahead (for launches of at most one tile per CU); else which operand
 // gets a third LDS stage and a prefetch distance of two K steps (0 none, 1 activations, 2 weights).
 template <int BM, int BN, int WM, int WN, int EPI, int SMEM, bool NT, int AMODE, int DEEP>
 __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, int m0, int n0) {
@@ -250,7 +251,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   constexpr int WL = BN / 8 / NW;
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TN % 32 == 0, "tile/waves mismatch");
 
-  constexpr int XS = DEEP == 1 ? 3 : 2, WS = DEEP == 2 ? 3 : 2;   // LDS stages per operand
+  constexpr int XS = DEEP == 3 ? 4 : (DEEP == 1 ? 3 : 2), WS = DEEP == 3 ? 4 : (DEEP == 2 ? 3 : 2);   // LDS stages per operand
   unsigned char *sX = smem;                        // [XS][BM][128 B]
   unsigned char *sW = smem + XS * BM * 128;        // [WS][BN][128 B]
 
@@ -388,9 +389,15 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   // step kt a wave has then issued ... shallow(kt+1), deep(kt+2) as its newest loads, and since vector-memory
   // operations complete in order, waiting until at most the loads of deep(kt+2) are outstanding means
   // everything step kt+1 reads has landed.  Slots: stage kt % 2, or kt % 3 for the deep operand.
+  // DEEP == 3 (a launch of at most one tile per CU, where nothing but the tile's own requests hides the latency of
+  // its operands): four stages for both, slot kt % 4; after the barrier that ends step kt the loads of step kt+4 go
+  // into the slot just read, and the wait before that barrier lets the loads of steps kt+2 and kt+3 stay in flight.
   constexpr int NDEEP = DEEP == 1 ? XL : (DEEP == 2 ? WL : 0);       // load instructions of one deep tile
+  constexpr int LPS = XL + WL;                                       // load instructions of one K step
   auto issue_next = [&](int kt, int s2, int s3) {    // after the barrier that ends step kt (s2 = kt % 2, s3 = kt % 3)
-    if (DEEP == 0) {
+    if (DEEP == 3) {
+      if (kt + 4 < nk) { issue_x(kt + 4, kt & 3); issue_w(kt + 4, kt & 3); }
+    } else if (DEEP == 0) {
       if (kt + 2 < nk) { issue_x(kt + 2, s2); issue_w(kt + 2, s2); }
     } else if (DEEP == 1) {
       if (kt + 2 < nk) issue_w(kt + 2, s2);
@@ -407,14 +414,18 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   if (1 < nk) { issue_x(1, 1); issue_w(1, 1); }
   if (DEEP == 1 && 2 < nk) issue_x(2, 2);
   if (DEEP == 2 && 2 < nk) issue_w(2, 2);
+  if (DEEP == 3) {
+    if (2 < nk) { issue_x(2, 2); issue_w(2, 2); }
+    if (3 < nk) { issue_x(3, 3); issue_w(3, 3); }
+  }
   rd_x(0, 0, 0);
   rd_w(0, 0, 0, wlo);
   int s3 = 0;                                      // kt % 3
   for (int kt = 0; kt < nk; ++kt) {
     const int s2 = kt & 1;
     const int s3n = s3 == 2 ? 0 : s3 + 1;
-    const int xs = DEEP == 1 ? s3 : s2, xs1 = DEEP == 1 ? s3n : s2 ^ 1;     // activation slots of steps kt, kt+1
-    const int ws = DEEP == 2 ? s3 : s2, ws1 = DEEP == 2 ? s3n : s2 ^ 1;     // weight slots
+    const int xs = DEEP == 3 ? (kt & 3) : (DEEP == 1 ? s3 : s2), xs1 = DEEP == 3 ? ((kt + 1) & 3) : (DEEP == 1 ? s3n : s2 ^ 1);   // activation slots of steps kt, kt+1
+    const int ws = DEEP == 3 ? (kt & 3) : (DEEP == 2 ? s3 : s2), ws1 = DEEP == 3 ? ((kt + 1) & 3) : (DEEP == 2 ? s3n : s2 ^ 1);   // weight slots
     __builtin_amdgcn_sched_barrier(0);
     // (t = 0, lo): read the upper weight fragments of step 0
     __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0), placed BEFORE the next reads so it only waits for older ones
@@ -436,7 +447,12 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
     mm(0, wlo, 1);
     WF_SCHED(FBH);
     // this step's stages fully read; my part of the tiles of step kt+1 landed (deep(kt+2) may still be in flight)
-    if (DEEP != 0 && kt + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0070 | NDEEP);   // vmcnt(NDEEP) lgkmcnt(0)
+    if (DEEP == 3) {                                  // loads of steps kt+2 and kt+3, as far as they exist, may stay in flight
+      constexpr int W2 = 2 * LPS, W1 = LPS;           // vmcnt: bits 3:0 and 15:14 of the immediate
+      if (kt + 3 < nk) __builtin_amdgcn_s_waitcnt(0x0070 | (W2 & 15) | ((W2 >> 4) << 14));
+      else if (kt + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0070 | (W1 & 15) | ((W1 >> 4) << 14));
+      else __builtin_amdgcn_s_waitcnt(0x0070);
+    } else if (DEEP != 0 && kt + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0070 | NDEEP);   // vmcnt(NDEEP) lgkmcnt(0)
     else __builtin_amdgcn_s_waitcnt(0x0070);                                    // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -462,7 +478,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __builtin_amdgcn_s_barrier();                    // every wave is done reading the last K step
   unsigned char *stg = smem + wave * (TM * 256);   // TM rows x 256 bytes (<= 16 KB per wave)
-  static_assert(NDEEP < 16 && NW * TM * 256 <= SMEM && (XS * BM + WS * BN) * 128 <= SMEM, "staging does not fit in the LDS stages");
+  static_assert(NDEEP < 16 && 2 * LPS < 64 && NW * TM * 256 <= SMEM && (XS * BM + WS * BN) * 128 <= SMEM, "staging does not fit in the LDS stages");
   const int mw0 = m0 + wm * TM, nw0 = n0 + wn * TN;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
     constexpr int RB = TN * 2;                     // row bytes (bf16)
@@ -628,7 +644,7 @@ __host__ __device__ inline bool dl_unit(const GemmArgs &p, int bid, int tiles_m,
 
 // LDS bytes of a direct-load kernel: its operand stages, or the epilogue's per-wave transposition slices if those are larger.
 constexpr int dl_smem_bytes(int bm, int bn, int nw, int tm, int deep) {
-  const int stages = (2 * (bm + bn) + (deep == 1 ? bm : (deep == 2 ? bn : 0))) * 128;
+  const int stages = deep == 3 ? 4 * (bm + bn) * 128 : (2 * (bm + bn) + (deep == 1 ? bm : (deep == 2 ? bn : 0))) * 128;
   const int slices = nw * tm * 256;
   return stages > slices ? stages : slices;
 }
@@ -702,6 +718,18 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
         case EPI_BIAS_GELU: return nt ? launch_dl<320, 256, 4, 2, EPI_BIAS_GELU, true>(a, s) : launch_dl<320, 256, 4, 2, EPI_BIAS_GELU>(a, s);
         case EPI_BIAS_RESID: return launch_dl<320, 256, 4, 2, EPI_BIAS_RESID>(a, s);
         default: break;     // fp32 store: the 256-row tile below
+      }
+    }
+    // At most one 128 x 128 tile per CU: nothing but the tile's own requests hides the latency of its operands, and the
+    // LDS of the second workgroup a CU could hold is free, so the operands get four stages.
+    const bool lone = !big && (long)((a.M + 127) / 128) * (a.N / 128) <= 256 && a.K >= 4 * BK;
+    if (lone) {
+      switch (epi) {
+        case EPI_BIAS: return launch_dl<128, 128, 2, 2, EPI_BIAS, false, A_PLAIN, 3>(a, s);
+        case EPI_BIAS_GELU: return launch_dl<128, 128, 2, 2, EPI_BIAS_GELU, false, A_PLAIN, 3>(a, s);
+        case EPI_BIAS_RESID: return launch_dl<128, 128, 2, 2, EPI_BIAS_RESID, false, A_PLAIN, 3>(a, s);
+        case EPI_BIAS_F32: return launch_dl<128, 128, 2, 2, EPI_BIAS_F32, false, A_PLAIN, 3>(a, s);
+        default: return hipErrorInvalidValue;
       }
     }
     switch (epi) {

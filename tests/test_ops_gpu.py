@@ -22,7 +22,9 @@ def _rel(got, ref):
 # (the last two) the row count of a 64-stream prompt prefill, where the small tile has to fill the chip
 LINEAR_SHAPES = [(75, 384, 384), (300, 1152, 384), (1000, 128, 1536), (257, 256, 64),
                  (12500, 3840, 1280), (12345, 1280, 5120), (12301, 5120, 1280),
-                 (6401, 1280, 1280), (6400, 1280, 5120), (10001, 2560, 640)]
+                 (6401, 1280, 1280), (6400, 1280, 5120), (10001, 2560, 640),
+                 # at most one 128 x 128 tile per CU: the four-stage operand ring, incl. its shortest K (4 and 5 steps)
+                 (2600, 1024, 4096), (4951, 768, 256), (1500, 2048, 320)]
 
 
 def test_linear_shapes_reach_every_tile_family():
