@@ -57,7 +57,9 @@ typedef struct {
   int32_t d_mlp;                 /* multiple of 128                                                */
   int32_t hush_frames;           /* H >= 0; 0 disables the append (padded-window baseline)         */
   int32_t max_streams;           /* capacity: streams per call                                     */
-  int32_t max_total_frames;      /* capacity: sum over streams of (n_frames + H) per call          */
+  int32_t max_total_frames;      /* capacity: sum over streams of (n_frames + H) per call; the
+                                    widest activation matrix of such a batch must stay under 4 GiB:
+                                    (max_total_frames / 2 + 256) * max(d_mlp, d_model) * 2 < 2^32  */
   int32_t max_frames_per_stream; /* capacity: n_frames + H of any one stream                       */
   int32_t precision;             /* WF_PRECISION_*                                                 */
   float   ln_eps;                /* LayerNorm epsilon; <= 0 selects 1e-5                           */
@@ -214,6 +216,7 @@ int wf_gemm_tile_choice(int32_t M, int32_t N, int32_t *tile_m, int32_t *tile_n);
  *                   K % 64 == 0.  epilogue 0: out [M, N] in the activation type; 1: GELU, same type;
  *                   2: out is fp32 [M, N] and is updated in place, out += a . w^T + bias.
  *                   (the projections of a transformer block: QKV, fc1, and out-projection / fc2)
+ *                   bf16: a and w must each be smaller than 4 GiB (WF_E_INVALID_ARG otherwise).
  * wf_op_layernorm   out[r, :] = (x[r, :] - mean) / sqrt(biased var + eps) * g + b, x fp32 [M, d],
  *                   out dtype WF_DTYPE_*; d % 4 == 0, d <= 2048.
  * wf_op_ln_linear   bf16 path, small batches only (M <= 1024, else WF_E_CAPACITY): out = epilogue(LayerNorm(x) . w^T + bias)

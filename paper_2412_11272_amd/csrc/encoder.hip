@@ -147,6 +147,13 @@ int check_config(const wf_config *c) {
   if (c->precision != WF_PRECISION_BF16 && c->precision != WF_PRECISION_F32)
     return fail(WF_E_INVALID_ARG, "precision = %d", c->precision);
   if (c->d_model > 2048) return fail(WF_E_INVALID_ARG, "d_model = %d exceeds the supported 2048", c->d_model);
+  // the MFMA GEMMs address an operand with 32-bit byte offsets: the largest one (the MLP's hidden activations of a
+  // full batch, rows padded to whole 256-row panels) must stay under 4 GiB
+  const int64_t max_tokens = ((int64_t)c->max_total_frames + 1) / 2 + 256;
+  const int64_t widest = c->d_mlp > c->d_model ? c->d_mlp : c->d_model;
+  if (max_tokens * widest * 2 >= ((int64_t)1 << 32))
+    return fail(WF_E_INVALID_ARG, "max_total_frames = %d with d_mlp = %d needs an activation matrix of 4 GiB or more; split the batch",
+                c->max_total_frames, c->d_mlp);
   return WF_OK;
 }
 
@@ -674,6 +681,8 @@ int wf_op_linear(int32_t precision, const void *a_dev, const void *w_dev, const 
   if (!a_dev || !w_dev || !bias_dev || !out_dev) return fail(WF_E_INVALID_ARG, "NULL pointer");
   if (M < 1 || N < 128 || N % 128 || K < 64 || K % 64) return fail(WF_E_INVALID_ARG, "need M >= 1, N %% 128 == 0, K %% 64 == 0");
   if (epilogue < 0 || epilogue > 2) return fail(WF_E_INVALID_ARG, "epilogue = %d", epilogue);
+  if (precision == WF_PRECISION_BF16 && ((int64_t)M * K * 2 >= ((int64_t)1 << 32) || (int64_t)N * K * 2 >= ((int64_t)1 << 32)))
+    return fail(WF_E_INVALID_ARG, "an operand of 4 GiB or more (M = %d, N = %d, K = %d): the bf16 GEMM addresses operands with 32-bit offsets", M, N, K);
   GemmArgs a{};
   a.A = a_dev; a.W = w_dev; a.bias = bias_dev; a.out = out_dev;
   a.M = M; a.N = N; a.K = K; a.lda = K; a.ldo = N;

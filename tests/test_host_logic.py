@@ -46,6 +46,11 @@ def test_config_check():
     for shape in synth.SHAPES.values():
         cfg = wf.make_config(shape, 50, 64, 200000, 3050)
         assert wf.config_check(cfg) == wf.WF_OK
+    # 32-bit operand offsets: (frames / 2 + 256) * d_mlp * 2 bytes must stay under 4 GiB (large-v3: ~838 k frames)
+    big = synth.SHAPES["large-v3"]
+    assert wf.config_check(wf.make_config(big, 50, 64, 830000, 3050)) == wf.WF_OK
+    assert wf.config_check(wf.make_config(big, 50, 64, 840000, 3050)) == wf.WF_E_INVALID_ARG
+    assert "4 GiB" in wf.last_error()
 
 
 def test_plan_batch_prefix_sums_and_paper_shape_facts():
