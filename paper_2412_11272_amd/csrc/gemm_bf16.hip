@@ -14,8 +14,12 @@
 //                         the masking is done in registers, so tiles go global -> registers -> LDS.
 //
 // Tiling: one workgroup computes a BM x BN tile and advances K by 64 through two LDS stages per operand
-// (three for the activations of the row-major residual projections, which then run two steps ahead); each wave
-// owns a (BM/WM) x (BN/WN) sub-tile.  The weight fragment is the MFMA's first operand and the activation
+// (three for the activations of the row-major residual projections on 256-row tiles, which then run two steps
+// ahead; four for both operands of a 128 x 128 launch with at most one tile per CU); each wave owns a
+// (BM/WM) x (BN/WN) sub-tile.  Tiles: 320 x 256 or 256 x 256 on 8 waves for large batches (these kernels are
+// bound by the operand lines they pull through L1, and 320 x 256 is the largest tile whose accumulators and
+// fragments fit 256 registers: 576 lines per K step instead of 640 for the same work), 128 x 128 on 4 waves,
+// two workgroups per CU, below that.  The weight fragment is the MFMA's first operand and the activation
 // fragment the second, so a lane ends up holding four consecutive output features of one token.
 // LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with (row >> 1) & 7.  The LDS
 // has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a time, so the 16 rows a
