@@ -333,13 +333,15 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
   // draws less power: on random operands a register-only loop sustains 1.97 against 1.76 PFLOP/s.)
   constexpr int TB = TM / 16, FB = TN / 16, FBH = FB / 2;
   static_assert(TM % 16 == 0 && TN % 32 == 0, "wave tile must be a multiple of 16 x 32");
+  // The accumulators start from the bias (a lane's four values of a block are four consecutive features), so the
+  // epilogue has no bias add left.
   f32x4 acc[TB][FB];
 #pragma unroll
-  for (int i = 0; i < TB; ++i)
+  for (int j = 0; j < FB; ++j) {
+    const f32x4 b = *(const f32x4 *)(p.bias + n0 + wn * TN + j * 16 + (lane >> 4) * 4);
 #pragma unroll
-    for (int j = 0; j < FB; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+    for (int i = 0; i < TB; ++i) acc[i][j] = b;
+  }
 
   const int nk = p.K / BK;
   const int l16 = lane & 15, lq = lane >> 4;       // row inside a 16-row block; which 8 of the 32 reduction indices
@@ -493,10 +495,7 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
 #pragma unroll
       for (int j = 0; j < FB; ++j) {
         const int nl = j * 16 + lq * 4;            // feature inside the wave's sub-tile
-        const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
-        f32x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e] + b[e];
+        f32x4 v = acc[i][j];
         if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
@@ -560,10 +559,9 @@ __device__ __forceinline__ void dl_tile(const GemmArgs &p, unsigned char *smem, 
         for (int jj = 0; jj < PW / 16; ++jj) {
           const int j = ps * (PW / 16) + jj;
           const int nl = j * 16 + lq * 4;
-          const f32x4 b = *(const f32x4 *)(p.bias + nw0 + nl);
           f32x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = EPI == EPI_BIAS_GELU_POS ? gelu_fast(acc[i][j][e] + b[e]) : acc[i][j][e] + b[e];
+          for (int e = 0; e < 4; ++e) v[e] = EPI == EPI_BIAS_GELU_POS ? gelu_fast(acc[i][j][e]) : acc[i][j][e];
           const int ch = (nl % PW) >> 2;           // 16-byte chunk inside the pass
           *(f32x4 *)(stg + r * RB + ((ch ^ (r & (CPR - 1))) << 4)) = v;
         }
