@@ -208,6 +208,14 @@ int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32
 int wf_gemm_tile_choice(int32_t M, int32_t N, int32_t *tile_m, int32_t *tile_n);
 
 /*
+ * Diagnostic, host only: the GELU the bf16 kernels apply in their epilogues (erf form by a clamped odd polynomial, no
+ * transcendental instruction), evaluated on the host with the same source code; out[i] = GELU(z[i]) for n HOST
+ * values.  A test bounds its distance from the exact erf form (Section "Operations": the encoder is the stock
+ * Whisper one, whose activation is the erf GELU).
+ */
+int wf_gelu_host(const float *z, float *out, int32_t n);
+
+/*
  * Operator-level entry points: single steps of the encoder on caller-provided DEVICE buffers, for
  * per-operator checks and micro-benchmarks.  precision selects the kernel family and the element
  * type of activations and weights (WF_PRECISION_BF16: bf16, WF_PRECISION_F32: fp32).

@@ -101,7 +101,7 @@ EXPORTS = ["wf_encoder_create", "wf_encode_batch", "wf_encoder_destroy", "wf_las
            "wf_rounds_destroy", "wf_run_rounds",
            "wf_beam_pruner_create", "wf_beam_pruner_step", "wf_beam_pruner_reset", "wf_beam_prune_session",
            "wf_beam_pruner_destroy", "wf_op_attention_noalloc",
-           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_gemm_tile_choice", "wf_device_info", "wf_op_ln_linear"]
+           "wf_encoder_set_graphs", "wf_encoder_graph_stats", "wf_gemm_tile_map", "wf_gemm_tile_choice", "wf_gelu_host", "wf_device_info", "wf_op_ln_linear"]
 
 
 def lib() -> C.CDLL:
@@ -153,6 +153,7 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     L.wf_gemm_tile_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _ip, C.c_int32]
     L.wf_gemm_tile_choice.argtypes = [C.c_int32, C.c_int32, _ip, _ip]
+    L.wf_gelu_host.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int32]
     L.wf_encoder_set_graphs.argtypes = [C.c_void_p, C.c_int32]
     _lp = C.POINTER(C.c_int64)
     L.wf_encoder_graph_stats.argtypes = [C.c_void_p, _lp, _lp, _lp]
@@ -592,6 +593,15 @@ def gemm_tile_choice(M: int, N: int) -> tuple:
     tm, tn = C.c_int32(0), C.c_int32(0)
     _check(lib().wf_gemm_tile_choice(M, N, C.byref(tm), C.byref(tn)))
     return tm.value, tn.value
+
+
+def gelu_host(z: np.ndarray) -> np.ndarray:
+    """The bf16 kernels' GELU evaluated on the host by the library's own code (host only)."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    out = np.empty_like(z)
+    fp = C.POINTER(C.c_float)
+    _check(lib().wf_gelu_host(z.ctypes.data_as(fp), out.ctypes.data_as(fp), z.size))
+    return out
 
 
 def device_info() -> dict:

@@ -3,6 +3,7 @@
 // include/wf_encoder.h.  Everything device-side is in the kernel files; this file only sequences
 // them on the caller's stream.
 #include "host_runtime.h"
+#include "device_utils.h"
 
 #include <cmath>
 #include <mutex>
@@ -666,6 +667,12 @@ int wf_gemm_tile_map(int32_t M, int32_t N, int32_t tile_m, int32_t tile_n, int32
   const int n = gemm_dl_tile_map(M, N, tile_m, tile_n, units, capacity);
   if (n < 0) return fail(WF_E_CAPACITY, "more work units than capacity = %d", capacity);
   return n;
+}
+
+int wf_gelu_host(const float *z, float *out, int32_t n) {
+  if (n < 0 || (n > 0 && (!z || !out))) return fail(WF_E_INVALID_ARG, "NULL pointer or negative count");
+  for (int32_t i = 0; i < n; ++i) out[i] = gelu_fast(z[i]);
+  return WF_OK;
 }
 
 int wf_gemm_tile_choice(int32_t M, int32_t N, int32_t *tile_m, int32_t *tile_n) {

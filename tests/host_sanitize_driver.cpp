@@ -151,6 +151,7 @@ int main() {
       printf(" %d", wf_op_ln_linear(nullptr, nullptr, nullptr, 1e-5f, nullptr, nullptr, nullptr, 1, 128, 64, 0, nullptr));
       printf(" %d", wf_gemm_tile_map(256, 256, 256, 256, nullptr, 0));
       printf(" %d", wf_gemm_tile_choice(256, 256, nullptr, nullptr));
+      printf(" %d", wf_gelu_host(nullptr, nullptr, 3));
       printf(" %d", wf_op_attention(0, nullptr, nullptr, nullptr, 1, 1, nullptr));
       printf(" %d", wf_op_attention_noalloc(0, nullptr, nullptr, nullptr, 1, 1, nullptr));
       printf(" %d", wf_rounds_create(nullptr, nullptr, nullptr));

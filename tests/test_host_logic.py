@@ -148,3 +148,23 @@ def test_gemm_tile_choice_follows_the_last_round_of_the_chip():
     with pytest.raises(wf.WfError):
         wf.gemm_tile_choice(100, 100)
 
+
+def test_kernel_gelu_stays_close_to_the_erf_form():
+    """The polynomial GELU of the bf16 epilogues, run on the host by the library's own code, against the oracle's erf
+    form: absolute error <= 1.5e-4 for |z| <= 4 and <= 6e-5 |z| beyond (Phi saturates at 0.99994 past the clamp),
+    relative error <= 5e-4 wherever |GELU| > 0.05 (a quarter of the half-ulp of the bf16 value it is rounded to),
+    exact zero at zero, and GELU(z) - GELU(-z) = z."""
+    from oracle import encoder_oracle as O
+    z = np.concatenate([np.linspace(-12, 12, 200001), [0.0, 1e-30, -1e-30, 50.0, -50.0]]).astype(np.float32)
+    got = wf.gelu_host(z).astype(np.float64)
+    ref = O.gelu(z.astype(np.float64))
+    err = np.abs(got - ref)
+    assert err[np.abs(z) <= 4].max() <= 1.5e-4
+    far = np.abs(z) > 4
+    assert (err[far] / np.abs(z[far])).max() <= 6e-5
+    big = np.abs(ref) > 0.05
+    assert (err[big] / np.abs(ref[big])).max() <= 5e-4
+    assert wf.gelu_host(np.zeros(1))[0] == 0.0
+    zz = np.linspace(0, 10, 1001).astype(np.float32)
+    np.testing.assert_allclose(wf.gelu_host(zz) - wf.gelu_host(-zz), zz, rtol=0, atol=4e-6)
+
