@@ -750,15 +750,19 @@ hipError_t launch_gemm_bf16(const GemmArgs &a, AMode amode, Epilogue epi, hipStr
   }
   if (a.C % 8 != 0 || 3 * a.C > a.K || !a.row_src || !a.row_flags) return hipErrorInvalidValue;
   // Taps that are whole K steps (C a multiple of 64, no padding after the third tap) go through the
-  // direct-load kernel: a masked tap is then a whole 16-byte load redirected to a zero source.
-  const bool direct = big && a.C % BK == 0 && 3 * a.C == a.K && !a.a_panels && !a.w_panels && !a.out_panels;
+  // direct-load kernel: a masked tap is then a whole 16-byte load redirected to a zero source.  Whether a shape
+  // qualifies does not depend on M: all tile sizes of that kernel add up a row in the same order, so a row's bits
+  // do not depend on how many rows share the launch (a batch cut into lanes gives the result of the whole batch).
+  const bool direct = a.C % BK == 0 && 3 * a.C == a.K && !a.a_panels && !a.w_panels && !a.out_panels;
   switch (epi) {
     case EPI_BIAS_GELU:
-      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU, false, A_CONV3>(a, s);
+      if (direct) return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU, false, A_CONV3>(a, s)
+                             : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU, false, A_CONV3>(a, s);
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU>(a, s) : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU>(a, s);
     case EPI_BIAS_GELU_POS:
       if (!a.pos || !a.row_pos) return hipErrorInvalidValue;
-      if (direct) return launch_dl<256, 256, 4, 2, EPI_BIAS_GELU_POS, false, A_CONV3, 1>(a, s);
+      if (direct) return big ? launch_dl<256, 256, 4, 2, EPI_BIAS_GELU_POS, false, A_CONV3, 1>(a, s)
+                             : launch_dl<128, 128, 2, 2, EPI_BIAS_GELU_POS, false, A_CONV3>(a, s);
       return big ? launch_cfg<256, 256, 4, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s)
                  : launch_cfg<128, 128, 2, 2, A_CONV3, EPI_BIAS_GELU_POS>(a, s);
     default: return hipErrorInvalidValue;

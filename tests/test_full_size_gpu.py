@@ -27,7 +27,7 @@ def _run(name):
         out2, _ = enc.encode(mel, offs, nf, out_dtype=torch.bfloat16)
         torch.cuda.synchronize()
         assert torch.equal(out, out2)                     # deterministic run to run
-        for lanes in (1, 3):                              # and independent of how the batch is cut into lanes
+        for lanes in (1, 3, 4):                           # and independent of how the batch is cut into lanes
             enc.set_lanes(lanes)
             out3, _ = enc.encode(mel, offs, nf, out_dtype=torch.bfloat16)
             torch.cuda.synchronize()
