@@ -13,7 +13,7 @@
 //     [16 w, 16 w + 16) with one 32x32x16 MFMA, and the four partial tiles are added in a fixed order through LDS
 //     at the end (deterministic);
 //   * operand chunks are requested eight (widest tile: four) K steps ahead into registers, so the K loop runs at the rate the chunks
-//     arrive instead of one memory latency per step;
+//     arrive instead of one memory latency per step, and two K steps are staged in LDS per barrier;
 //   * A_LN: the activation operand is LayerNorm(x) of an fp32 matrix x, normalised on the way into LDS.  The
 //     workgroup first computes mean and 1/sqrt(var + eps) of its 32 rows (one pass, sums shifted by the row's first
 //     element so that the variance does not cancel), then every chunk is (x - mean) * rstd * gamma + beta rounded
@@ -36,9 +36,14 @@ template <int AMODE, int EPI, int NB>
 __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
   constexpr int TN = NB * SBN;                                               // tile width in columns
   constexpr int DEPTH = NB >= 4 ? 4 : 8;                                     // K steps in flight (register ring)
-  __shared__ __attribute__((aligned(16))) unsigned char sA[2][SBM * 128];   // [stage][row][64 bf16]
-  __shared__ __attribute__((aligned(16))) unsigned char sW[2][TN * 128];
-  __shared__ __attribute__((aligned(16))) float sPart[4][SBM][TN + 4];       // the four waves' partial tiles
+  // SPB K steps are staged in LDS per barrier, double-buffered (NS = 2 SPB stages per operand); the four waves'
+  // partial tiles reuse the same memory after the K loop.
+  constexpr int SPB = 2, NS = 2 * SPB;               // (four per barrier measured the same as two)
+  constexpr int STAGE_BYTES = NS * (SBM + TN) * 128, PART_BYTES = 4 * SBM * (TN + 4) * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char sMem[STAGE_BYTES > PART_BYTES ? STAGE_BYTES : PART_BYTES];
+  unsigned char(*sA)[SBM * 128] = (unsigned char(*)[SBM * 128])sMem;                     // [stage][row][64 bf16]
+  unsigned char(*sW)[TN * 128] = (unsigned char(*)[TN * 128])(sMem + NS * SBM * 128);
+  float(*sPart)[SBM][TN + 4] = (float(*)[SBM][TN + 4])sMem;
   __shared__ __attribute__((aligned(16))) float sGain[AMODE == A_LN ? kMaxLnK : 4], sShift[AMODE == A_LN ? kMaxLnK : 4];
 
   const int tiles_n = p.N / TN;
@@ -91,8 +96,8 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
       xreg[slot][1] = *(const f32x4 *)(xptr + kt * SBK + 4);
     }
   };
-  auto commit = [&](int kt, int slot) {          // registers -> LDS stage kt & 1
-    unsigned char *dA = sA[kt & 1] + lds_off, *dW = sW[kt & 1] + lds_off;
+  auto commit = [&](int kt, int slot) {          // registers -> LDS stage kt % NS
+    unsigned char *dA = sA[kt & (NS - 1)] + lds_off, *dW = sW[kt & (NS - 1)] + lds_off;
 #pragma unroll
     for (int j = 0; j < NB; ++j) *(u32x4 *)(dW + j * SBN * 128) = wreg[slot][j];
     if constexpr (AMODE == A_LN) {
@@ -118,7 +123,7 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[j][i] = 0.0f;
 #pragma unroll
-  for (int d = 0; d < DEPTH - 1; ++d)
+  for (int d = 0; d < DEPTH; ++d)
     if (d < nk) request(d, d);
   // ---- A_LN: statistics of the tile's 32 rows (after the first operand requests, so that their latencies overlap).
   // Eight threads per row, each over every eighth 32-byte piece, eight pieces requested at a time.
@@ -164,23 +169,37 @@ __global__ void __launch_bounds__(256) gemm_small_kernel(GemmArgs p) {
   }
   // fragment of wave `wave`: row l32, k slice 16 * wave + 8 * lg .. + 7 = chunk 2 * wave + lg
   const int frag_off = l32 * 128 + (((2 * wave + lg) ^ ((l32 >> 1) & 7)) << 4);
+  // SPB K steps per barrier: they are written to their stages, their register slots are refilled with the steps
+  // DEPTH further on, and after one barrier all of them are multiplied.  The group after the next one reuses these
+  // stages; a wave gets there only through the next barrier, which every wave reaches after its reads of this group.
+  auto multiply = [&](int kt) {
+    const bf16x8 xf = *(const bf16x8 *)(sA[kt & (NS - 1)] + frag_off);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const bf16x8 wf = *(const bf16x8 *)(sW[kt & (NS - 1)] + j * SBN * 128 + frag_off);
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[j], 0, 0, 0);
+    }
+  };
+  static_assert(DEPTH % SPB == 0, "the ring is walked SPB slots at a time");
   for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {            // unrolled by the ring depth: register slots are compile-time
+    for (int d = 0; d < DEPTH; d += SPB) {       // unrolled by the ring depth: register slots are compile-time
       const int kt = kt0 + d;
       if (kt < nk) {
-        commit(kt, d);
-        if (kt + DEPTH - 1 < nk) request(kt + DEPTH - 1, (d + DEPTH - 1) % DEPTH);
-        __syncthreads();                         // stage kt & 1 is complete; stage (kt + 1) & 1 is no longer read
-        const bf16x8 xf = *(const bf16x8 *)(sA[kt & 1] + frag_off);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-          const bf16x8 wf = *(const bf16x8 *)(sW[kt & 1] + j * SBN * 128 + frag_off);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[j], 0, 0, 0);
-        }
+        for (int q = 0; q < SPB; ++q)
+          if (kt + q < nk) commit(kt + q, d + q);
+#pragma unroll
+        for (int q = 0; q < SPB; ++q)
+          if (kt + q + DEPTH < nk) request(kt + q + DEPTH, d + q);
+        __syncthreads();                         // the stages of steps kt .. kt + SPB - 1 are complete
+#pragma unroll
+        for (int q = 0; q < SPB; ++q)
+          if (kt + q < nk) multiply(kt + q);
       }
     }
   }
+  __syncthreads();                               // every wave is done with the stages: the partial tiles may overwrite them
 
   // ---- the four k slices are added in wave order; lane holds token l32, features 8 (i / 4) + 4 lg + i % 4 of block j
 #pragma unroll
