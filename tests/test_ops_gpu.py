@@ -63,6 +63,53 @@ def test_linear_bf16(M, N, K, epi):
     assert _rel(got, ref) < tol
 
 
+def _linear_case(M, N, K, epi, seed):
+    import torch
+    rng = np.random.default_rng(seed)
+    a = _bf16_round(rng.standard_normal((M, K)))
+    w = _bf16_round(rng.standard_normal((N, K)) * 0.05)
+    bias = rng.standard_normal(N).astype(np.float32)
+    ref = O.linear(a.float().numpy().astype(np.float64), w.float().numpy().astype(np.float64), bias.astype(np.float64))
+    if epi == 2:
+        x0 = rng.standard_normal((M, N)).astype(np.float32)
+        out = torch.from_numpy(x0).cuda()
+        ref = x0.astype(np.float64) + ref
+    else:
+        out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        if epi == 1:
+            ref = O.gelu(ref)
+    wf.op_linear(wf.WF_PRECISION_BF16, a.cuda(), w.cuda(), torch.from_numpy(bias).cuda(), out, epi)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.all(np.isfinite(got)), (M, N, K, epi)
+    assert _rel(got, ref) < (5e-3 if epi != 2 else 2e-5), (M, N, K, epi, wf.gemm_tile_choice(M, N))
+
+
+def test_linear_bf16_at_the_edges_of_every_kernel_choice():
+    """Row counts on both sides of each switch of the launcher: small-batch kernel / 128 x 128 tile (1024 rows), one
+    tile per CU with four operand stages / two per CU (256 tiles of 128 x 128), 128 x 128 / large tile (160 tiles of
+    256 x 256), 256 / 320 rows; K loops of 1 to 5 steps; every epilogue."""
+    cases = [(1024, 256, 192), (1025, 256, 192), (1025, 128, 64), (4096, 1024, 256), (4097, 1024, 320),
+             (3840, 2560, 128), (4096, 2560, 128), (4097, 2560, 64), (5100, 2560, 256), (5121, 2560, 192),
+             (8191, 1280, 320), (8193, 1280, 64), (6400, 2560, 128), (6657, 2560, 192)]
+    picks = set()
+    for i, (M, N, K) in enumerate(cases):
+        picks.add(wf.gemm_tile_choice(M, N))
+        for epi in (0, 1, 2):
+            _linear_case(M, N, K, epi, 1000 + 3 * i + epi)
+    assert picks == {(0, 0), (128, 128), (256, 256), (320, 256)}
+
+
+def test_linear_bf16_random_shapes():
+    """Seeded random shapes across all kernel choices (row counts 1 .. 9000, widths and depths in the kernels' units)."""
+    rng = np.random.default_rng(77)
+    for i in range(24):
+        M = int(rng.integers(1, 9001))
+        N = 128 * int(rng.integers(1, 21))
+        K = 64 * int(rng.integers(1, 17))
+        _linear_case(M, N, K, int(rng.integers(0, 3)), 2000 + i)
+
+
 @pytest.mark.parametrize("M,N,K", [(75, 384, 384), (300, 1152, 240), (1000, 128, 1536)])
 @pytest.mark.parametrize("epi", [0, 1, 2])
 def test_linear_f32(M, N, K, epi):
