@@ -106,6 +106,7 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
   float m_run = -INFINITY;     // running max of the raw logits of this lane's query
   float l_run = 0.0f;          // this lane's share of the running sum (the lane^32 partner has the rest)
   const float c = p.scale * 1.4426950408889634f;   // exp(s*scale) = exp2(s*c)
+  const float lazy = 8.0f / c;
 
   // Tile loads: 16 instructions of 8 rows per tile (8 for K, 8 for V), 4 per wave.
   const int lrow = lane >> 3;
@@ -180,7 +181,10 @@ __global__ void __launch_bounds__(256) attention_bf16_kernel(AttnArgs p) {
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb2][r]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
     const float m_new = fmaxf(m_run, tmax);       // finite: every tile has at least one valid key
-    if (__any(m_new > m_run)) {                   // rescale only when some query's maximum moved
+    // The softmax reference m_run only has to bound the logits from below by a known margin: it follows the running
+    // maximum when some query's maximum has moved up by more than 8 / c (weights up to 2^8 until then; fp32 sums and
+    // bf16 weights have the range), which spares most rescales of the accumulators.
+    if (__any(m_new > m_run + lazy)) {
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
       l_run *= alpha;
 #pragma unroll
